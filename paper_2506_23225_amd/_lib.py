@@ -1,0 +1,59 @@
+"""Loads ``libmglu.so`` (the C ABI of include/mglu.h) through ctypes.
+
+There is no fallback: if the library has not been built, loading raises.
+"""
+import ctypes
+import os
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libmglu.so")
+
+MGLU_OK = 0
+MGLU_F32, MGLU_BF16 = 0, 1
+MGLU_W_KN, MGLU_W_NK = 0, 1
+
+
+class MgluDesc(ctypes.Structure):
+    _fields_ = [("tokens", ctypes.c_int32), ("d_model", ctypes.c_int32), ("d_ff", ctypes.c_int32),
+                ("n_masks", ctypes.c_int32), ("dtype", ctypes.c_int), ("w_layout", ctypes.c_int)]
+
+
+# every symbol include/mglu.h declares: name -> (restype, argtypes)
+_P = ctypes.c_void_p
+_D = ctypes.POINTER(MgluDesc)
+_SZ = ctypes.c_size_t
+SIGNATURES = {
+    "mglu_format_version": (ctypes.c_int, []),
+    "mglu_packed_weight_bytes": (_SZ, [_D]),
+    "mglu_pack_weights": (ctypes.c_int, [_D, _P, _P, _P]),
+    "mglu_packed_mask_bytes": (_SZ, [_D]),
+    "mglu_pack_masks": (ctypes.c_int, [_D, _P, _P, _P]),
+    "mglu_workspace_bytes": (_SZ, [_D]),
+    "mglu_forward": (ctypes.c_int, [_D, _P, _P, _P, _P, _P, _SZ, _P]),
+    "mglu_forward_bool_workspace_bytes": (_SZ, [_D]),
+    "mglu_forward_bool": (ctypes.c_int, [_D, _P, _P, _P, _P, _P, _SZ, _P]),
+    "mglu_projections": (ctypes.c_int, [_D, _P, _P, _P, _P, _P, _P, _P, _SZ, _P]),
+    "swiglu_forward": (ctypes.c_int, [_D, _P, _P, _P, _P, _P, _SZ, _P]),
+    "mglu_stream_read": (ctypes.c_int, [_P, _SZ, _P, _P]),
+    "mglu_last_error": (ctypes.c_char_p, []),
+    "mglu_status_string": (ctypes.c_char_p, [ctypes.c_int]),
+}
+
+_lib = None
+
+
+def load():
+    """The loaded library, with argument types set.  Raises if libmglu.so is missing."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(
+                "%s is missing: build it with `python -m paper_2506_23225_amd.build` "
+                "(there is no fallback path)" % LIB_PATH)
+        lib = ctypes.CDLL(LIB_PATH)
+        for name, (restype, argtypes) in SIGNATURES.items():
+            fn = getattr(lib, name)
+            fn.restype = restype
+            fn.argtypes = argtypes
+        _lib = lib
+    return _lib

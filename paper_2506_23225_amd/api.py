@@ -1,0 +1,140 @@
+"""Thin Python binding of libmglu: same names as the C ABI, argument marshalling only.
+
+torch is used for device memory and the current HIP stream; every step of the
+MGLU path runs in the library's kernels.  Tensors must live on the GPU and be
+contiguous.
+"""
+import torch
+
+from . import _lib
+from ._lib import MgluDesc
+
+_DTYPE = {torch.float32: _lib.MGLU_F32, torch.bfloat16: _lib.MGLU_BF16}
+_LAYOUT = {"kn": _lib.MGLU_W_KN, "nk": _lib.MGLU_W_NK}
+
+
+class MgluError(RuntimeError):
+    def __init__(self, status, message):
+        super().__init__("libmglu status %d (%s): %s" % (
+            status, _lib.load().mglu_status_string(status).decode(), message))
+        self.status = status
+
+
+def _check(status):
+    if status != _lib.MGLU_OK:
+        raise MgluError(status, _lib.load().mglu_last_error().decode())
+
+
+def _stream(t):
+    return torch.cuda.current_stream(t.device).cuda_stream
+
+
+def _ptr(t, name):
+    if t is None:
+        return None
+    if not t.is_cuda:
+        raise ValueError("%s must be a GPU tensor" % name)
+    if not t.is_contiguous():
+        raise ValueError("%s must be contiguous" % name)
+    return t.data_ptr()
+
+
+def make_desc(tokens, d_model, d_ff, n_masks, dtype, w_layout="kn"):
+    return MgluDesc(int(tokens), int(d_model), int(d_ff), int(n_masks), _DTYPE[dtype], _LAYOUT[w_layout])
+
+
+def mglu_format_version():
+    return _lib.load().mglu_format_version()
+
+
+def mglu_packed_weight_bytes(desc):
+    return _lib.load().mglu_packed_weight_bytes(desc)
+
+
+def mglu_packed_mask_bytes(desc):
+    return _lib.load().mglu_packed_mask_bytes(desc)
+
+
+def mglu_workspace_bytes(desc):
+    return _lib.load().mglu_workspace_bytes(desc)
+
+
+def mglu_forward_bool_workspace_bytes(desc):
+    return _lib.load().mglu_forward_bool_workspace_bytes(desc)
+
+
+def mglu_pack_weights(desc, W, packed=None):
+    """W [d_model,d_ff] ('kn') or [d_ff,d_model] ('nk') -> packed uint8 buffer."""
+    if packed is None:
+        packed = torch.empty(mglu_packed_weight_bytes(desc), dtype=torch.uint8, device=W.device)
+    _check(_lib.load().mglu_pack_weights(desc, _ptr(W, "W"), _ptr(packed, "packed"), _stream(W)))
+    return packed
+
+
+def mglu_pack_masks(desc, masks, packed=None):
+    """masks uint8/bool [n_masks,d_model,d_ff] ('kn') or [n_masks,d_ff,d_model] ('nk') -> packed buffer."""
+    if masks.dtype == torch.bool:
+        masks = masks.view(torch.uint8)
+    if packed is None:
+        packed = torch.empty(mglu_packed_mask_bytes(desc), dtype=torch.uint8, device=masks.device)
+    _check(_lib.load().mglu_pack_masks(desc, _ptr(masks, "masks"), _ptr(packed, "packed"), _stream(masks)))
+    return packed
+
+
+def _workspace(desc, device, workspace):
+    need = mglu_workspace_bytes(desc)
+    if workspace is None and need:
+        workspace = torch.zeros(need, dtype=torch.uint8, device=device)
+    return workspace, (workspace.numel() if workspace is not None else 0)
+
+
+def mglu_forward(desc, x, W_packed, masks_packed, out=None, workspace=None):
+    if out is None:
+        out = torch.empty(desc.tokens, desc.d_ff, dtype=x.dtype, device=x.device)
+    workspace, ws_bytes = _workspace(desc, x.device, workspace)
+    _check(_lib.load().mglu_forward(desc, _ptr(x, "x"), _ptr(W_packed, "W_packed"),
+                                    _ptr(masks_packed, "masks_packed"), _ptr(out, "out"),
+                                    _ptr(workspace, "workspace"), ws_bytes, _stream(x)))
+    return out
+
+
+def mglu_forward_bool(desc, x, W, masks, out=None, workspace=None):
+    if masks.dtype == torch.bool:
+        masks = masks.view(torch.uint8)
+    if out is None:
+        out = torch.empty(desc.tokens, desc.d_ff, dtype=x.dtype, device=x.device)
+    if workspace is None:
+        workspace = torch.zeros(mglu_forward_bool_workspace_bytes(desc), dtype=torch.uint8, device=x.device)
+    _check(_lib.load().mglu_forward_bool(desc, _ptr(x, "x"), _ptr(W, "W"), _ptr(masks, "masks"),
+                                         _ptr(out, "out"), _ptr(workspace, "workspace"),
+                                         workspace.numel(), _stream(x)))
+    return out
+
+
+def mglu_projections(desc, x, W_packed, masks_packed, workspace=None):
+    """Returns (t [T,d], gate [n_masks,T,d], value [n_masks,T,d]) in fp32."""
+    T, d, n = desc.tokens, desc.d_ff, desc.n_masks
+    t = torch.empty(T, d, dtype=torch.float32, device=x.device)
+    gate = torch.empty(n, T, d, dtype=torch.float32, device=x.device)
+    value = torch.empty(n, T, d, dtype=torch.float32, device=x.device)
+    workspace, ws_bytes = _workspace(desc, x.device, workspace)
+    _check(_lib.load().mglu_projections(desc, _ptr(x, "x"), _ptr(W_packed, "W_packed"),
+                                        _ptr(masks_packed, "masks_packed"), _ptr(t, "t"),
+                                        _ptr(gate, "gate"), _ptr(value, "value"),
+                                        _ptr(workspace, "workspace"), ws_bytes, _stream(x)))
+    return t, gate, value
+
+
+def swiglu_forward(desc, x, Wg_packed, Wv_packed, out=None, workspace=None):
+    if out is None:
+        out = torch.empty(desc.tokens, desc.d_ff, dtype=x.dtype, device=x.device)
+    workspace, ws_bytes = _workspace(desc, x.device, workspace)
+    _check(_lib.load().swiglu_forward(desc, _ptr(x, "x"), _ptr(Wg_packed, "Wg_packed"),
+                                      _ptr(Wv_packed, "Wv_packed"), _ptr(out, "out"),
+                                      _ptr(workspace, "workspace"), ws_bytes, _stream(x)))
+    return out
+
+
+def mglu_stream_read(buf, sink):
+    _check(_lib.load().mglu_stream_read(_ptr(buf, "buf"), buf.numel() * buf.element_size(),
+                                        _ptr(sink, "sink"), _stream(buf)))

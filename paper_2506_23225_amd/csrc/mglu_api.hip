@@ -1,0 +1,266 @@
+// C ABI of libmglu (declared in include/mglu.h): argument checks and kernel dispatch.
+// No exception crosses the boundary; nothing here allocates device memory.
+#include <stdarg.h>
+#include <stdio.h>
+
+#include "../../include/mglu.h"
+#include "mglu_common.hpp"
+#include "mglu_kernels.hpp"
+
+namespace {
+
+thread_local char g_error[512] = "";
+
+mglu_status fail(mglu_status code, const char *fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_error, sizeof(g_error), fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+// Shape part of the descriptor (everything but `tokens`).
+mglu_status check_shape(const mglu_desc *d, bool need_masks)
+{
+    if (!d) return fail(MGLU_ERR_INVALID_ARG, "descriptor is NULL");
+    if (d->dtype != MGLU_F32 && d->dtype != MGLU_BF16)
+        return fail(MGLU_ERR_INVALID_ARG, "dtype %d is neither MGLU_F32 nor MGLU_BF16", (int)d->dtype);
+    if (d->w_layout != MGLU_W_KN && d->w_layout != MGLU_W_NK)
+        return fail(MGLU_ERR_INVALID_ARG, "w_layout %d is neither MGLU_W_KN nor MGLU_W_NK", (int)d->w_layout);
+    if (d->d_model < 1 || d->d_ff < 1)
+        return fail(MGLU_ERR_INVALID_ARG, "d_model=%d and d_ff=%d must be >= 1", d->d_model, d->d_ff);
+    if (need_masks) {
+        if (d->n_masks < 1) return fail(MGLU_ERR_INVALID_ARG, "n_masks=%d must be >= 1", d->n_masks);
+        if (d->n_masks > 8) return fail(MGLU_ERR_UNSUPPORTED, "n_masks=%d: at most 8 masks are supported", d->n_masks);
+    }
+    const long nb = mglu::ceil_div(d->d_ff, mglu::kColBlock), nc = mglu::ceil_div(d->d_model, mglu::kChunkK);
+    if (nb > 0x7fffffffL / 64 || nb * nc > 0x7fffffffL / 8)
+        return fail(MGLU_ERR_UNSUPPORTED, "d_model=%d x d_ff=%d is too large", d->d_model, d->d_ff);
+    return MGLU_OK;
+}
+
+mglu_status check_forward(const mglu_desc *d, bool need_masks)
+{
+    mglu_status s = check_shape(d, need_masks);
+    if (s != MGLU_OK) return s;
+    if (d->tokens < 1) return fail(MGLU_ERR_INVALID_ARG, "tokens=%d must be >= 1", d->tokens);
+    const int lane_k = d->dtype == MGLU_F32 ? 4 : 8;
+    if (d->d_model % lane_k != 0)
+        return fail(MGLU_ERR_UNSUPPORTED, "d_model=%d must be a multiple of %d so that rows of x stay 16-byte aligned",
+                    d->d_model, lane_k);
+    if ((long)d->tokens * d->d_ff > 0x7fffffff00L)
+        return fail(MGLU_ERR_UNSUPPORTED, "tokens=%d x d_ff=%d is too large", d->tokens, d->d_ff);
+    return MGLU_OK;
+}
+
+mglu_status check_ptr(const void *p, const char *name)
+{
+    if (!p) return fail(MGLU_ERR_INVALID_ARG, "%s is NULL", name);
+    if (!aligned16(p)) return fail(MGLU_ERR_INVALID_ARG, "%s is not 16-byte aligned", name);
+    return MGLU_OK;
+}
+
+mglu_status hip_result(hipError_t e, const char *what)
+{
+    if (e == hipSuccess) return MGLU_OK;
+    return fail(MGLU_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
+}
+
+mglu::StreamParams stream_params(const mglu_desc *d)
+{
+    mglu::StreamParams p = {};
+    p.T = d->tokens;
+    p.h = d->d_model;
+    p.d = d->d_ff;
+    p.n_masks = d->n_masks;
+    p.NB = (int)mglu::ceil_div(d->d_ff, mglu::kColBlock);
+    p.NC = (int)mglu::ceil_div(d->d_model, mglu::kChunkK);
+    return p;
+}
+
+mglu::PackParams pack_params(const mglu_desc *d, const void *src, void *dst)
+{
+    mglu::PackParams p = {};
+    p.src = src;
+    p.dst = dst;
+    p.h = d->d_model;
+    p.d = d->d_ff;
+    p.n_masks = d->n_masks;
+    p.NB = (int)mglu::ceil_div(d->d_ff, mglu::kColBlock);
+    p.NC = (int)mglu::ceil_div(d->d_model, mglu::kChunkK);
+    p.nk = d->w_layout == MGLU_W_NK;
+    return p;
+}
+
+#define MGLU_TRY(expr)                      \
+    do {                                    \
+        mglu_status s_ = (expr);            \
+        if (s_ != MGLU_OK) return s_;       \
+    } while (0)
+
+}  // namespace
+
+extern "C" {
+
+int mglu_format_version(void) { return 1; }
+
+size_t mglu_packed_weight_bytes(const mglu_desc *desc)
+{
+    if (check_shape(desc, false) != MGLU_OK) return 0;
+    const size_t nb = mglu::ceil_div(desc->d_ff, mglu::kColBlock), nc = mglu::ceil_div(desc->d_model, mglu::kChunkK);
+    return nb * nc * mglu::kColBlock * mglu::kChunkK * (desc->dtype == MGLU_F32 ? 4 : 2);
+}
+
+size_t mglu_packed_mask_bytes(const mglu_desc *desc)
+{
+    if (check_shape(desc, true) != MGLU_OK) return 0;
+    const size_t nb = mglu::ceil_div(desc->d_ff, mglu::kColBlock), nc = mglu::ceil_div(desc->d_model, mglu::kChunkK);
+    return nb * nc * mglu::kWave * mglu::round_up_masks(desc->n_masks) * sizeof(uint32_t);
+}
+
+mglu_status mglu_pack_weights(const mglu_desc *desc, const void *W_dev, void *packed_dev, void *stream)
+{
+    MGLU_TRY(check_shape(desc, false));
+    MGLU_TRY(check_ptr(W_dev, "W_dev"));
+    MGLU_TRY(check_ptr(packed_dev, "packed_dev"));
+    return hip_result(mglu::launch_pack_weights(pack_params(desc, W_dev, packed_dev), desc->dtype == MGLU_F32,
+                                                static_cast<hipStream_t>(stream)),
+                      "mglu_pack_weights launch");
+}
+
+mglu_status mglu_pack_masks(const mglu_desc *desc, const uint8_t *masks_dev, void *packed_dev, void *stream)
+{
+    MGLU_TRY(check_shape(desc, true));
+    MGLU_TRY(check_ptr(masks_dev, "masks_dev"));
+    MGLU_TRY(check_ptr(packed_dev, "packed_dev"));
+    return hip_result(mglu::launch_pack_masks(pack_params(desc, masks_dev, packed_dev), desc->dtype == MGLU_F32,
+                                              static_cast<hipStream_t>(stream)),
+                      "mglu_pack_masks launch");
+}
+
+size_t mglu_workspace_bytes(const mglu_desc *desc)
+{
+    if (check_shape(desc, false) != MGLU_OK) return 0;
+    return 0;
+}
+
+mglu_status mglu_forward(const mglu_desc *desc, const void *x_dev, const void *W_packed_dev,
+                         const void *masks_packed_dev, void *out_dev, void *workspace_dev,
+                         size_t workspace_bytes, void *stream)
+{
+    MGLU_TRY(check_forward(desc, true));
+    MGLU_TRY(check_ptr(x_dev, "x_dev"));
+    MGLU_TRY(check_ptr(W_packed_dev, "W_packed_dev"));
+    MGLU_TRY(check_ptr(masks_packed_dev, "masks_packed_dev"));
+    MGLU_TRY(check_ptr(out_dev, "out_dev"));
+    (void)workspace_dev;
+    (void)workspace_bytes;
+    mglu::StreamParams p = stream_params(desc);
+    p.x = x_dev;
+    p.w = W_packed_dev;
+    p.m = static_cast<const uint32_t *>(masks_packed_dev);
+    p.out = out_dev;
+    return hip_result(mglu::launch_stream(p, desc->dtype == MGLU_F32, mglu::kModeMglu, static_cast<hipStream_t>(stream)),
+                      "mglu_forward launch");
+}
+
+size_t mglu_forward_bool_workspace_bytes(const mglu_desc *desc)
+{
+    const size_t w = mglu_packed_weight_bytes(desc), m = mglu_packed_mask_bytes(desc);
+    if (w == 0 || m == 0) return 0;
+    return align_up(w, 256) + align_up(m, 256) + align_up(mglu_workspace_bytes(desc), 256);
+}
+
+mglu_status mglu_forward_bool(const mglu_desc *desc, const void *x_dev, const void *W_dev,
+                              const uint8_t *masks_dev, void *out_dev, void *workspace_dev,
+                              size_t workspace_bytes, void *stream)
+{
+    MGLU_TRY(check_forward(desc, true));
+    MGLU_TRY(check_ptr(workspace_dev, "workspace_dev"));
+    const size_t need = mglu_forward_bool_workspace_bytes(desc);
+    if (workspace_bytes < need)
+        return fail(MGLU_ERR_WORKSPACE, "workspace has %zu bytes, mglu_forward_bool needs %zu", workspace_bytes, need);
+    char *ws = static_cast<char *>(workspace_dev);
+    void *wp = ws;
+    void *mp = ws + align_up(mglu_packed_weight_bytes(desc), 256);
+    char *fw = static_cast<char *>(mp) + align_up(mglu_packed_mask_bytes(desc), 256);
+    MGLU_TRY(mglu_pack_weights(desc, W_dev, wp, stream));
+    MGLU_TRY(mglu_pack_masks(desc, masks_dev, mp, stream));
+    return mglu_forward(desc, x_dev, wp, mp, out_dev, fw, workspace_bytes - (size_t)(fw - ws), stream);
+}
+
+mglu_status mglu_projections(const mglu_desc *desc, const void *x_dev, const void *W_packed_dev,
+                             const void *masks_packed_dev, float *t_dev, float *gate_dev, float *value_dev,
+                             void *workspace_dev, size_t workspace_bytes, void *stream)
+{
+    MGLU_TRY(check_forward(desc, true));
+    MGLU_TRY(check_ptr(x_dev, "x_dev"));
+    MGLU_TRY(check_ptr(W_packed_dev, "W_packed_dev"));
+    MGLU_TRY(check_ptr(masks_packed_dev, "masks_packed_dev"));
+    if (t_dev) MGLU_TRY(check_ptr(t_dev, "t_dev"));
+    if (gate_dev) MGLU_TRY(check_ptr(gate_dev, "gate_dev"));
+    if (value_dev) MGLU_TRY(check_ptr(value_dev, "value_dev"));
+    (void)workspace_dev;
+    (void)workspace_bytes;
+    mglu::StreamParams p = stream_params(desc);
+    p.x = x_dev;
+    p.w = W_packed_dev;
+    p.m = static_cast<const uint32_t *>(masks_packed_dev);
+    p.proj_t = t_dev;
+    p.proj_gate = gate_dev;
+    p.proj_value = value_dev;
+    return hip_result(mglu::launch_stream(p, desc->dtype == MGLU_F32, mglu::kModeProjections,
+                                          static_cast<hipStream_t>(stream)),
+                      "mglu_projections launch");
+}
+
+mglu_status swiglu_forward(const mglu_desc *desc, const void *x_dev, const void *Wg_packed_dev,
+                           const void *Wv_packed_dev, void *out_dev, void *workspace_dev,
+                           size_t workspace_bytes, void *stream)
+{
+    MGLU_TRY(check_forward(desc, false));
+    MGLU_TRY(check_ptr(x_dev, "x_dev"));
+    MGLU_TRY(check_ptr(Wg_packed_dev, "Wg_packed_dev"));
+    MGLU_TRY(check_ptr(Wv_packed_dev, "Wv_packed_dev"));
+    MGLU_TRY(check_ptr(out_dev, "out_dev"));
+    (void)workspace_dev;
+    (void)workspace_bytes;
+    mglu::StreamParams p = stream_params(desc);
+    p.x = x_dev;
+    p.w = Wg_packed_dev;
+    p.w2 = Wv_packed_dev;
+    p.out = out_dev;
+    return hip_result(mglu::launch_stream(p, desc->dtype == MGLU_F32, mglu::kModeSwiglu, static_cast<hipStream_t>(stream)),
+                      "swiglu_forward launch");
+}
+
+mglu_status mglu_stream_read(const void *buf_dev, size_t bytes, uint32_t *sink_dev, void *stream)
+{
+    MGLU_TRY(check_ptr(buf_dev, "buf_dev"));
+    MGLU_TRY(check_ptr(sink_dev, "sink_dev"));
+    if (bytes == 0 || bytes % 16 != 0)
+        return fail(MGLU_ERR_INVALID_ARG, "bytes=%zu must be a positive multiple of 16", bytes);
+    return hip_result(mglu::launch_stream_read(buf_dev, bytes, sink_dev, static_cast<hipStream_t>(stream)),
+                      "mglu_stream_read launch");
+}
+
+const char *mglu_last_error(void) { return g_error; }
+
+const char *mglu_status_string(mglu_status s)
+{
+    switch (s) {
+    case MGLU_OK: return "ok";
+    case MGLU_ERR_INVALID_ARG: return "invalid argument";
+    case MGLU_ERR_UNSUPPORTED: return "unsupported";
+    case MGLU_ERR_WORKSPACE: return "workspace too small";
+    case MGLU_ERR_HIP: return "HIP runtime error";
+    }
+    return "unknown status";
+}
+
+}  // extern "C"

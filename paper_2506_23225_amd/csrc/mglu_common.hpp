@@ -1,0 +1,152 @@
+// Shared definitions of the MGLU kernels for gfx950: packed-format constants,
+// MFMA fragment traits and the fused epilogue (Eq. 3 of the paper).
+//
+// Packed formats (both produced by mglu_pack.hip, consumed by the kernels)
+// -----------------------------------------------------------------------
+// The logical weight matrix W[k][j] (k < d_model, j < d_ff) is cut into column
+// blocks of 16 (index jb) and reduction chunks of 128 (index kc), zero-padded to
+// those multiples.  One (jb, kc) pair is a "chunk": 16 x 128 elements.
+//
+//   bf16 weights  [jb][kc][tile t<4][lane<64][e<8]  : W[128kc + 32t + 8(lane/16) + e][16jb + lane%16]
+//   fp32 weights  [jb][kc][tile t<8][lane<64][e<4]  : W[128kc + 16t + 4(lane/16) + e][16jb + lane%16]
+//
+// so that one wavefront load of 16 bytes per lane is a contiguous 1 KiB run and
+// lands directly in the A-operand layout of v_mfma_f32_16x16x32_bf16 (row =
+// lane%16, eight consecutive k per lane) or, for fp32, of four
+// v_mfma_f32_16x16x4_f32 (row = lane%16, k = lane/16, one per e).
+//
+//   masks  [jb][kc][lane<64][word<NMP]  uint32,  NMP = n_masks rounded up to 1,2,4,8
+//
+// A lane's NMP words hold the NMP x 32 mask bits of the 32 weight elements that
+// lane holds in the chunk.  bf16: the elements form 16 register pairs
+// P = 4t + e/2 (low half e even, high half e odd); bit for (P, mask i, half hf) is
+// at linear = P*NMP + i -> word linear/16, bit (linear%16) + 16*hf, so one shift
+// brings both bits of a pair to the two bf16 sign positions 15 and 31.
+// fp32: element E = 4t + e, linear = E*NMP + i -> word linear/32, bit linear%32.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace mglu {
+
+constexpr int kColBlock = 16;   // output columns per MFMA tile
+constexpr int kChunkK = 128;    // reduction elements per chunk
+constexpr int kWave = 64;
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+
+__host__ __device__ constexpr int round_up_masks(int n) { return n <= 1 ? 1 : n <= 2 ? 2 : n <= 4 ? 4 : 8; }
+__host__ __device__ constexpr long ceil_div(long a, long b) { return (a + b - 1) / b; }
+
+// ---- fp32 <-> bf16 ---------------------------------------------------------------------
+__device__ inline float bf16_bits_to_f32(uint32_t b) { return __uint_as_float(b << 16); }
+
+// round to nearest, ties to even; NaN stays NaN
+__device__ inline uint32_t f32_to_bf16_bits(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x40u;
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return u >> 16;
+}
+
+// ---- Swish, beta = 1:  z * sigmoid(z) = z / (1 + exp(-z)) --------------------------------
+__device__ inline float swish(float z)
+{
+    // exp(-z) overflows to +inf for z < -88 and the quotient is then -0, the right limit.
+    return __fdividef(z, 1.0f + __expf(-z));
+}
+
+// ---- element traits ------------------------------------------------------------------------
+// A chunk is TILES fragments per lane; a fragment is 16 bytes of W (A operand) or x (B operand).
+struct Bf16Traits {
+    typedef u32x4 frag;                       // 4 registers, each a (k, k+1) pair of bf16
+    static constexpr int TILES = 4;           // 32 k per tile
+    static constexpr int TILE_K = 32;
+    static constexpr int LANE_K = 8;          // consecutive k one lane holds per tile
+    static constexpr int ELEM_BYTES = 2;
+
+    __device__ static inline f32x4 mma(frag a, frag b, f32x4 c)
+    {
+        return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a),
+                                                       __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+    }
+
+    // W fragment of tile t with the sign of every element whose bit in mask i is set flipped.
+    template <int NMP>
+    __device__ static inline frag flip(frag w, const uint32_t (&m)[NMP], int t, int i)
+    {
+        frag r;
+#pragma unroll
+        for (int p = 0; p < 4; ++p) {
+            const int lin = (4 * t + p) * NMP + i;
+            r[p] = w[p] ^ ((m[lin >> 4] << (15 - (lin & 15))) & 0x80008000u);
+        }
+        return r;
+    }
+
+    __device__ static inline void store4(void *out, long idx, f32x4 v)
+    {
+        u32x2 pk;
+        pk.x = f32_to_bf16_bits(v.x) | (f32_to_bf16_bits(v.y) << 16);
+        pk.y = f32_to_bf16_bits(v.z) | (f32_to_bf16_bits(v.w) << 16);
+        *reinterpret_cast<u32x2 *>(static_cast<uint16_t *>(out) + idx) = pk;
+    }
+    __device__ static inline void store1(void *out, long idx, float v)
+    {
+        static_cast<uint16_t *>(out)[idx] = (uint16_t)f32_to_bf16_bits(v);
+    }
+};
+
+struct F32Traits {
+    typedef f32x4 frag;                       // 4 consecutive k, one register each
+    static constexpr int TILES = 8;           // 16 k per tile
+    static constexpr int TILE_K = 16;
+    static constexpr int LANE_K = 4;
+    static constexpr int ELEM_BYTES = 4;
+
+    __device__ static inline f32x4 mma(frag a, frag b, f32x4 c)
+    {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) c = __builtin_amdgcn_mfma_f32_16x16x4f32(a[e], b[e], c, 0, 0, 0);
+        return c;
+    }
+
+    template <int NMP>
+    __device__ static inline frag flip(frag w, const uint32_t (&m)[NMP], int t, int i)
+    {
+        frag r;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const int lin = (4 * t + e) * NMP + i;
+            r[e] = __uint_as_float(__float_as_uint(w[e]) ^ ((m[lin >> 5] << (31 - (lin & 31))) & 0x80000000u));
+        }
+        return r;
+    }
+
+    __device__ static inline void store4(void *out, long idx, f32x4 v)
+    {
+        *reinterpret_cast<f32x4 *>(static_cast<float *>(out) + idx) = v;
+    }
+    __device__ static inline void store1(void *out, long idx, float v) { static_cast<float *>(out)[idx] = v; }
+};
+
+// ---- what a launch computes ---------------------------------------------------------------
+enum Mode {
+    kModeMglu = 0,         // out = sum_i swish(gate_i) * value_i            (Eq. 3)
+    kModeProjections = 1,  // t, gate_i, value_i in fp32                      (Alg. 1's z)
+    kModeSwiglu = 2        // out = swish(x Wg) * (x Wv), two weight streams  (Eq. 1)
+};
+
+// Sign-flip form of the complement trick (Alg. 1 writes s_i and t - s_i): with
+// t = sum v and dsum_i = sum (1 - 2 M_i) v over the same terms in the same order,
+//   gate_i = (t - dsum_i) / 2,   value_i = (t + dsum_i) / 2.
+// An all-gate mask gives dsum_i = -t bit for bit (rounding is sign-symmetric), hence
+// value_i = 0 exactly; an all-value mask gives gate_i = 0 exactly.
+__device__ inline float gate_of(float t, float dsum) { return 0.5f * (t - dsum); }
+__device__ inline float value_of(float t, float dsum) { return 0.5f * (t + dsum); }
+
+}  // namespace mglu

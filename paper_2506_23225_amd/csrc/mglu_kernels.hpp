@@ -1,0 +1,37 @@
+// Host-callable launchers of the MGLU kernels (internal to libmglu).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace mglu {
+
+struct StreamParams {
+    const void *x;        // [T][h]
+    const void *w;        // packed weights (SwiGLU: the gate matrix)
+    const void *w2;       // SwiGLU only: packed value matrix
+    const uint32_t *m;    // packed masks
+    void *out;            // [T][d]
+    float *proj_t;        // projections mode: [T][d], may be null
+    float *proj_gate;     // [n_masks][T][d], may be null
+    float *proj_value;    // [n_masks][T][d], may be null
+    int T, h, d, n_masks;
+    int NB;               // column blocks  = ceil(d / 16)
+    int NC;               // reduction chunks = ceil(h / 128)
+};
+
+struct PackParams {
+    const void *src;      // W or mask bytes, layout per `nk`
+    void *dst;
+    int h, d, n_masks;
+    int NB, NC;
+    int nk;               // 0: [h][d] (masks [n][h][d]); 1: [d][h] (masks [n][d][h])
+};
+
+hipError_t launch_stream(const StreamParams &p, bool is_f32, int mode, hipStream_t stream);
+int stream_max_token_blocks(int nmp, bool is_f32);
+hipError_t launch_stream_read(const void *buf, size_t bytes, uint32_t *sink, hipStream_t stream);
+
+hipError_t launch_pack_weights(const PackParams &p, bool is_f32, hipStream_t stream);
+hipError_t launch_pack_masks(const PackParams &p, bool is_f32, hipStream_t stream);
+
+}  // namespace mglu

@@ -1,0 +1,121 @@
+// One-time set-up kernels: re-tile W and bit-pack the masks into the order the MGLU
+// kernels stream them in (formats: see mglu_common.hpp).
+//
+// Paper: section "FlashMGLU", item "Packs mask bits" -- the n_m mask bits of a weight
+// element are combined so that one load brings all mask information for a block of
+// weights.  The paper spends one 8-bit integer per element whatever n_m is; here
+// exactly n_m (rounded up to 1, 2, 4, 8) bits per element are stored, the figure its
+// memory-load table counts, and their order is the register order of the consuming
+// lane.  Masks and weights are fixed at inference, so none of this is on the
+// per-token path.
+#include "mglu_common.hpp"
+#include "mglu_kernels.hpp"
+
+namespace mglu {
+
+// One thread writes one 16-byte fragment (LANE_K consecutive k of one column).
+template <typename Tr, typename elem_t>
+__global__ __launch_bounds__(256) void pack_weights_kernel(PackParams p)
+{
+    const long total = (long)p.NB * p.NC * Tr::TILES * kWave;
+    const long gid = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (gid >= total) return;
+    const int lane = (int)(gid % kWave);
+    long rest = gid / kWave;
+    const int t = (int)(rest % Tr::TILES);
+    rest /= Tr::TILES;
+    const int kc = (int)(rest % p.NC);
+    const int jb = (int)(rest / p.NC);
+    const int j = jb * kColBlock + (lane & 15);
+    const int k0 = kc * kChunkK + t * Tr::TILE_K + (lane >> 4) * Tr::LANE_K;
+    const elem_t *src = static_cast<const elem_t *>(p.src);
+    elem_t v[Tr::LANE_K];
+#pragma unroll
+    for (int e = 0; e < Tr::LANE_K; ++e) {
+        const int k = k0 + e;
+        elem_t w = 0;
+        if (j < p.d && k < p.h) w = p.nk ? src[(long)j * p.h + k] : src[(long)k * p.d + j];
+        v[e] = w;
+    }
+    elem_t *dst = static_cast<elem_t *>(p.dst) + gid * Tr::LANE_K;
+#pragma unroll
+    for (int e = 0; e < Tr::LANE_K; ++e) dst[e] = v[e];
+}
+
+// One thread builds the NMP mask words of one lane of one chunk.
+template <typename Tr, int NMP>
+__global__ __launch_bounds__(256) void pack_masks_kernel(PackParams p)
+{
+    const long total = (long)p.NB * p.NC * kWave;
+    const long gid = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (gid >= total) return;
+    const int lane = (int)(gid % kWave);
+    const long rest = gid / kWave;
+    const int kc = (int)(rest % p.NC);
+    const int jb = (int)(rest / p.NC);
+    const int j = jb * kColBlock + (lane & 15);
+    const uint8_t *src = static_cast<const uint8_t *>(p.src);
+    const long plane = (long)p.h * p.d;
+
+    uint32_t words[NMP];
+#pragma unroll
+    for (int w = 0; w < NMP; ++w) words[w] = 0u;
+
+#pragma unroll
+    for (int t = 0; t < Tr::TILES; ++t) {
+#pragma unroll
+        for (int e = 0; e < Tr::LANE_K; ++e) {
+            const int k = kc * kChunkK + t * Tr::TILE_K + (lane >> 4) * Tr::LANE_K + e;
+            if (j >= p.d || k >= p.h) continue;
+            const long off = p.nk ? (long)j * p.h + k : (long)k * p.d + j;
+#pragma unroll
+            for (int i = 0; i < NMP; ++i) {
+                if (i >= p.n_masks) break;
+                const uint32_t bit = src[i * plane + off] != 0 ? 1u : 0u;
+                if (Tr::ELEM_BYTES == 2) {
+                    const int lin = (4 * t + (e >> 1)) * NMP + i;  // register pair P = 4t + e/2
+                    words[lin >> 4] |= bit << ((lin & 15) + 16 * (e & 1));
+                } else {
+                    const int lin = (4 * t + e) * NMP + i;         // element E = 4t + e
+                    words[lin >> 5] |= bit << (lin & 31);
+                }
+            }
+        }
+    }
+    uint32_t *dst = static_cast<uint32_t *>(p.dst) + gid * NMP;
+#pragma unroll
+    for (int w = 0; w < NMP; ++w) dst[w] = words[w];
+}
+
+hipError_t launch_pack_weights(const PackParams &p, bool is_f32, hipStream_t stream)
+{
+    const int tiles = is_f32 ? F32Traits::TILES : Bf16Traits::TILES;
+    const long total = (long)p.NB * p.NC * tiles * kWave;
+    const unsigned blocks = (unsigned)ceil_div(total, 256);
+    if (is_f32)
+        hipLaunchKernelGGL((pack_weights_kernel<F32Traits, float>), dim3(blocks), dim3(256), 0, stream, p);
+    else
+        hipLaunchKernelGGL((pack_weights_kernel<Bf16Traits, uint16_t>), dim3(blocks), dim3(256), 0, stream, p);
+    return hipGetLastError();
+}
+
+template <typename Tr>
+static hipError_t launch_pack_masks_t(const PackParams &p, hipStream_t stream)
+{
+    const long total = (long)p.NB * p.NC * kWave;
+    const dim3 grid((unsigned)ceil_div(total, 256)), block(256);
+    switch (round_up_masks(p.n_masks)) {
+    case 1: hipLaunchKernelGGL((pack_masks_kernel<Tr, 1>), grid, block, 0, stream, p); break;
+    case 2: hipLaunchKernelGGL((pack_masks_kernel<Tr, 2>), grid, block, 0, stream, p); break;
+    case 4: hipLaunchKernelGGL((pack_masks_kernel<Tr, 4>), grid, block, 0, stream, p); break;
+    default: hipLaunchKernelGGL((pack_masks_kernel<Tr, 8>), grid, block, 0, stream, p); break;
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_pack_masks(const PackParams &p, bool is_f32, hipStream_t stream)
+{
+    return is_f32 ? launch_pack_masks_t<F32Traits>(p, stream) : launch_pack_masks_t<Bf16Traits>(p, stream);
+}
+
+}  // namespace mglu

@@ -1,0 +1,160 @@
+"""GPU parity: the HIP path (through the C ABI) against the fp64 CPU oracle, element by element."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import mglu_oracle as oracle
+from paper_2506_23225_amd import api, synth
+from tests.helpers import TOL, edge_columns, rel_err, to_np64
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def _run(x, W, masks, layout="kn", via_bool=False):
+    T, h = x.shape
+    n_m = masks.shape[0]
+    d = W.shape[1] if layout == "kn" else W.shape[0]
+    desc = api.make_desc(T, h, d, n_m, x.dtype, layout)
+    if via_bool:
+        return api.mglu_forward_bool(desc, x, W, masks)
+    Wp = api.mglu_pack_weights(desc, W)
+    Mp = api.mglu_pack_masks(desc, masks)
+    return api.mglu_forward(desc, x, Wp, Mp)
+
+
+def _check_full(x, W, masks, out, tol=None):
+    ref = oracle.mglu_forward(to_np64(x), to_np64(W), masks.cpu().numpy())
+    err = rel_err(to_np64(out), ref)
+    assert err <= (tol or TOL[x.dtype]), err
+    return err
+
+
+def _check_columns(x, W, masks, out, cols):
+    ci = torch.as_tensor(cols, device=W.device)
+    ref = oracle.mglu_forward(to_np64(x), to_np64(W[:, ci]), masks[:, :, ci].cpu().numpy())
+    err = rel_err(to_np64(out[:, ci]), ref)
+    assert err <= TOL[x.dtype], err
+    return err
+
+
+def test_tiny_fp32_config():
+    cfg = synth.config("tiny")
+    x, W, masks = synth.make_inputs(**cfg, seed=0, device=DEV)
+    out = _run(x, W, masks)
+    print("tiny fp32 rel err", _check_full(x, W, masks, out))
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("T,h,d,n_m", [
+    (1, 8, 1, 1), (1, 128, 16, 1), (3, 200, 50, 3), (16, 256, 688, 2), (17, 136, 17, 5),
+    (33, 1024, 100, 8), (5, 2048, 48, 4), (2, 520, 36, 7), (64, 384, 64, 1), (70, 256, 40, 2),
+])
+def test_ragged_shapes(dtype, T, h, d, n_m):
+    x, W, masks = synth.make_inputs(h, d, n_m, T, dtype=dtype, seed=T + h + d, device=DEV)
+    _check_full(x, W, masks, _run(x, W, masks))
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_nk_layout_and_bool_entry(dtype):
+    x, W, masks = synth.make_inputs(392, 72, 3, 4, dtype=dtype, seed=5, device=DEV)
+    ref = _run(x, W, masks)
+    Wt = W.t().contiguous()
+    Mt = masks.transpose(1, 2).contiguous()
+    assert torch.equal(_run(x, Wt, Mt, layout="nk"), ref)
+    assert torch.equal(_run(x, W, masks, via_bool=True), ref)
+    assert torch.equal(_run(x, Wt, Mt, layout="nk", via_bool=True), ref)
+    _check_full(x, W, masks, ref)
+
+
+def test_decode_gemv_config_full():
+    cfg = synth.config("decode_gemv")
+    x, W, masks = synth.make_inputs(**cfg, seed=0, device=DEV)
+    out = _run(x, W, masks)
+    print("decode_gemv rel err", _check_full(x, W, masks, out))
+
+
+@pytest.mark.parametrize("T", [1, 4, 16])
+def test_decode_8b_config_sampled(T):
+    cfg = synth.config("decode_8b", tokens=T)
+    x, W, masks = synth.make_inputs(**cfg, seed=0, device=DEV)
+    out = _run(x, W, masks)
+    print("decode_8b T=%d rel err" % T, _check_columns(x, W, masks, out, edge_columns(cfg["d_ff"])))
+
+
+@pytest.mark.parametrize("n_m,T", [(1, 1), (2, 32), (4, 1), (8, 32)])
+def test_large_config_sampled(n_m, T):
+    cfg = synth.config("large", n_masks=n_m, tokens=T)
+    x, W, masks = synth.make_inputs(**cfg, seed=0, device=DEV)
+    out = _run(x, W, masks)
+    print("large n_m=%d T=%d rel err" % (n_m, T),
+          _check_columns(x, W, masks, out, edge_columns(cfg["d_ff"], n_random=64)))
+
+
+def test_projections_partition_and_oracle():
+    """Alg. 1's z: gate_i + value_i = xW, and each branch matches the oracle's."""
+    x, W, masks = synth.make_inputs(512, 96, 4, 3, dtype="bf16", seed=11, device=DEV)
+    desc = api.make_desc(3, 512, 96, 4, x.dtype)
+    Wp, Mp = api.mglu_pack_weights(desc, W), api.mglu_pack_masks(desc, masks)
+    t, gate, value = api.mglu_projections(desc, x, Wp, Mp)
+    _, og, ov = oracle.mglu_forward(to_np64(x), to_np64(W), masks.cpu().numpy(), return_projections=True)
+    dense = to_np64(x) @ to_np64(W)
+    scale = np.abs(dense).max()
+    assert np.abs(to_np64(t) - dense).max() <= 1e-5 * scale
+    for i in range(4):
+        assert np.abs(to_np64(gate[i]) - og[i]).max() <= 1e-5 * scale
+        assert np.abs(to_np64(value[i]) - ov[i]).max() <= 1e-5 * scale
+        assert np.abs(to_np64(gate[i] + value[i]) - dense).max() <= 1e-5 * scale
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_degenerate_masks_and_inputs(dtype):
+    """Cases whose exact answer is 0.  All-value masks and one-hot inputs give 0 bit for bit.
+    An all-gate mask gives value_i = (t + dsum_i)/2 with dsum_i the sum of the negated terms;
+    the matrix cores' accumulation is not sign-symmetric to the last bit, so that case is held
+    to an absolute bound far below one output ulp instead: 1e-6 * |x|_2 * max|W| * sqrt(h)."""
+    h = 640
+    x, W, masks = synth.make_inputs(h, 80, 2, 2, dtype=dtype, seed=3, device=DEV)
+    ones = torch.ones_like(masks)
+    bound = 1e-6 * float(x.float().norm(dim=1).max()) * float(W.float().abs().max()) * h ** 0.5
+    assert float(_run(x, W, ones).float().abs().max()) <= bound   # all-gate: value branch empty
+    assert torch.count_nonzero(_run(x, W, 1 - ones)) == 0          # all-value: swish(0) = 0
+    xh = torch.zeros_like(x)
+    xh[0, 77] = -3.25
+    xh[1, 639] = 0.5
+    assert torch.count_nonzero(_run(xh, W, masks)) == 0            # one-hot rows
+    # an extra all-value route adds exactly nothing, an extra all-gate route at most the bound
+    base = _run(x, W, masks)
+    assert torch.equal(_run(x, W, torch.cat([masks, 1 - ones[:1]])), base)
+    more = _run(x, W, torch.cat([masks, ones[:1]]))
+    assert rel_err(to_np64(more), to_np64(base)) <= (1e-2 if dtype == "bf16" else 1e-5)
+
+
+def test_rows_independent_and_mask_order_and_determinism():
+    x, W, masks = synth.make_inputs(1024, 160, 4, 16, dtype="bf16", seed=4, device=DEV)
+    full = _run(x, W, masks)
+    assert torch.equal(_run(x, W, masks), full)                 # same bits on a second call
+    for tau in (0, 7, 15):
+        assert torch.equal(_run(x[tau:tau + 1].contiguous(), W, masks)[0], full[tau])
+    perm = _run(x, W, masks[[2, 0, 3, 1]].contiguous())
+    assert rel_err(to_np64(perm), to_np64(full)) <= 1e-2       # fp32 sum order differs, value does not
+
+
+@pytest.mark.parametrize("dtype,T", [("bf16", 1), ("bf16", 16), ("f32", 3)])
+def test_swiglu_reference_kernel(dtype, T):
+    xg, Wg, _ = synth.make_inputs(768, 208, 1, T, dtype=dtype, seed=6, device=DEV)
+    _, Wv, _ = synth.make_inputs(768, 208, 1, T, dtype=dtype, seed=7, device=DEV)
+    desc = api.make_desc(T, 768, 208, 1, xg.dtype)
+    out = api.swiglu_forward(desc, xg, api.mglu_pack_weights(desc, Wg), api.mglu_pack_weights(desc, Wv))
+    ref = oracle.swiglu_forward(to_np64(xg), to_np64(Wg), to_np64(Wv))
+    assert rel_err(to_np64(out), ref) <= TOL[xg.dtype]
+
+
+def test_single_mask_equals_swiglu_kernel_on_split_matrices():
+    """Eq. 2 vs Eq. 1 on the GPU: MGLU_1(W, M) against the two-matrix kernel fed W*M and W*(1-M)."""
+    x, W, masks = synth.make_inputs(512, 128, 1, 4, dtype="bf16", seed=8, device=DEV)
+    desc = api.make_desc(4, 512, 128, 1, x.dtype)
+    m = masks[0].to(W.dtype)
+    sw = api.swiglu_forward(desc, x, api.mglu_pack_weights(desc, (W * m).contiguous()),
+                            api.mglu_pack_weights(desc, (W * (1 - m)).contiguous()))
+    assert rel_err(to_np64(_run(x, W, masks)), to_np64(sw)) <= 1e-2
