@@ -6,7 +6,8 @@ import ctypes
 import os
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(HERE, "libmglu.so")
+# MGLU_LIBRARY_PATH selects another build of the same ABI (e.g. one compiled with other tuning macros).
+LIB_PATH = os.environ.get("MGLU_LIBRARY_PATH") or os.path.join(HERE, "libmglu.so")
 
 MGLU_OK = 0
 MGLU_F32, MGLU_BF16 = 0, 1

@@ -22,22 +22,46 @@
 #include "mglu_common.hpp"
 #include "mglu_kernels.hpp"
 
+// Tuning knobs (compile-time; the defaults are the measured best on MI355X).
+#ifndef MGLU_STREAM_MAX_WAVES
+#define MGLU_STREAM_MAX_WAVES 4   // wavefronts per workgroup = ways the reduction dimension is split
+#endif
+#ifndef MGLU_STREAM_WAVES_PER_EU
+#define MGLU_STREAM_WAVES_PER_EU 0  // 0: let the compiler pick the register budget
+#endif
+#ifndef MGLU_STREAM_PREFETCH_XLDS
+#define MGLU_STREAM_PREFETCH_XLDS 1  // chunks of loads in flight per wavefront when x sits in LDS
+#endif
+#if MGLU_STREAM_WAVES_PER_EU
+#define MGLU_STREAM_OCCUPANCY __attribute__((amdgpu_waves_per_eu(MGLU_STREAM_WAVES_PER_EU, MGLU_STREAM_WAVES_PER_EU)))
+#else
+#define MGLU_STREAM_OCCUPANCY
+#endif
+
 namespace mglu {
 
-template <typename Tr, int NMP, int TB, int MODE>
+// Registers of one chunk in flight: W (or the two SwiGLU matrices), the mask words and, when x
+// is not staged in LDS, the x fragments.
+template <typename Tr, int NMP, int TB, int MODE, bool XLDS>
 struct Chunk {
     typename Tr::frag w[Tr::TILES];
     typename Tr::frag w2[MODE == kModeSwiglu ? Tr::TILES : 1];
     uint32_t m[NMP];
-    typename Tr::frag x[TB][Tr::TILES];
+    typename Tr::frag x[XLDS ? 1 : TB][XLDS ? 1 : Tr::TILES];
 };
 
-template <typename Tr, int NMP, int TB, int MODE>
-__global__ __launch_bounds__(512) void stream_kernel(StreamParams p)
+// XLDS: the token block's rows of x are copied once into LDS in B-operand order and read from
+//       there tile by tile (needs TB == 1 and tokens * d_model small enough); otherwise every
+//       chunk loads its x fragments from global memory (L2 hits) next to W.
+// PF:   chunks of loads in flight ahead of the one being multiplied.
+template <typename Tr, int NMP, int TB, int MODE, bool XLDS, int PF>
+__global__ __launch_bounds__(512) MGLU_STREAM_OCCUPANCY void stream_kernel(StreamParams p)
 {
+    static_assert(!XLDS || TB == 1, "x is staged in LDS for a single token block only");
     constexpr int SETS = (MODE == kModeSwiglu) ? 2 : 1 + NMP;
     constexpr long CHUNK_BYTES = (long)kColBlock * kChunkK * Tr::ELEM_BYTES;
     typedef typename Tr::frag frag;
+    typedef Chunk<Tr, NMP, TB, MODE, XLDS> chunk_t;
     extern __shared__ f32x4 lds[];
 
     const int lane = threadIdx.x & 63;
@@ -46,6 +70,7 @@ __global__ __launch_bounds__(512) void stream_kernel(StreamParams p)
     const int r = lane & 15, q = lane >> 4;
     const int jb = blockIdx.x;
     const int tok0 = blockIdx.y * (16 * TB);
+    const int tc = (TB == 1) ? min(p.T - tok0, 16) : 16;  // token lanes that carry data
 
     const char *wbase = static_cast<const char *>(p.w) + (long)jb * p.NC * CHUNK_BYTES + lane * 16;
     const char *w2base = static_cast<const char *>(p.w2) + (long)jb * p.NC * CHUNK_BYTES + lane * 16;
@@ -60,13 +85,16 @@ __global__ __launch_bounds__(512) void stream_kernel(StreamParams p)
         xrow[tb] = static_cast<const char *>(p.x) + (long)(tok_ok[tb] ? tok : 0) * p.h * Tr::ELEM_BYTES;
     }
 
+    // LDS: [x fragments of this token block, XLDS only][hand-over area of the K-split reduction]
+    frag *lds_x = reinterpret_cast<frag *>(lds);
+    const int x_frags = XLDS ? p.NC * Tr::TILES * 4 * tc : 0;
+    f32x4 *lds_red = lds + x_frags;
+
     f32x4 acc[SETS][TB];
 #pragma unroll
     for (int s = 0; s < SETS; ++s)
 #pragma unroll
         for (int tb = 0; tb < TB; ++tb) acc[s][tb] = f32x4{0.f, 0.f, 0.f, 0.f};
-
-    typedef Chunk<Tr, NMP, TB, MODE> chunk_t;
 
     auto load_chunk = [&](chunk_t &c, int kc) {
         const char *wp = wbase + (long)kc * CHUNK_BYTES;
@@ -96,65 +124,119 @@ __global__ __launch_bounds__(512) void stream_kernel(StreamParams p)
                 c.m[0] = __builtin_nontemporal_load(mp);
             }
         }
+        if constexpr (!XLDS) {
 #pragma unroll
-        for (int tb = 0; tb < TB; ++tb)
+            for (int tb = 0; tb < TB; ++tb)
 #pragma unroll
-            for (int t = 0; t < Tr::TILES; ++t) {
-                const int k0 = kc * kChunkK + t * Tr::TILE_K + q * Tr::LANE_K;
-                frag v = frag{0, 0, 0, 0};
-                if (tok_ok[tb] && k0 < p.h)
-                    v = *reinterpret_cast<const frag *>(xrow[tb] + (long)k0 * Tr::ELEM_BYTES);
-                c.x[tb][t] = v;
-            }
+                for (int t = 0; t < Tr::TILES; ++t) {
+                    const int k0 = kc * kChunkK + t * Tr::TILE_K + q * Tr::LANE_K;
+                    frag v = frag{0, 0, 0, 0};
+                    if (tok_ok[tb] && k0 < p.h)
+                        v = *reinterpret_cast<const frag *>(xrow[tb] + (long)k0 * Tr::ELEM_BYTES);
+                    c.x[tb][t] = v;
+                }
+        }
     };
 
-    auto compute = [&](const chunk_t &c) {
+    auto compute = [&](const chunk_t &c, int kc) {
 #pragma unroll
         for (int t = 0; t < Tr::TILES; ++t) {
+            frag xf[TB];
+            if constexpr (XLDS) {
+                xf[0] = frag{0, 0, 0, 0};
+                if (r < tc) xf[0] = lds_x[((kc * Tr::TILES + t) * 4 + q) * tc + r];
+            } else {
 #pragma unroll
-            for (int tb = 0; tb < TB; ++tb) acc[0][tb] = Tr::mma(c.w[t], c.x[tb][t], acc[0][tb]);
+                for (int tb = 0; tb < TB; ++tb) xf[tb] = c.x[tb][t];
+            }
+#pragma unroll
+            for (int tb = 0; tb < TB; ++tb) acc[0][tb] = Tr::mma(c.w[t], xf[tb], acc[0][tb]);
             if constexpr (MODE == kModeSwiglu) {
 #pragma unroll
-                for (int tb = 0; tb < TB; ++tb) acc[1][tb] = Tr::mma(c.w2[t], c.x[tb][t], acc[1][tb]);
+                for (int tb = 0; tb < TB; ++tb) acc[1][tb] = Tr::mma(c.w2[t], xf[tb], acc[1][tb]);
             } else {
 #pragma unroll
                 for (int i = 0; i < NMP; ++i) {
                     const frag wf = Tr::template flip<NMP>(c.w[t], c.m, t, i);
 #pragma unroll
-                    for (int tb = 0; tb < TB; ++tb) acc[1 + i][tb] = Tr::mma(wf, c.x[tb][t], acc[1 + i][tb]);
+                    for (int tb = 0; tb < TB; ++tb) acc[1 + i][tb] = Tr::mma(wf, xf[tb], acc[1 + i][tb]);
                 }
             }
         }
     };
 
-    // ---- stream this wavefront's chunks, one chunk of loads in flight ahead of the math ----
-    {
-        int kc = wave;
-        if (kc < p.NC) {
-            chunk_t cur, nxt;
-            load_chunk(cur, kc);
-            for (;;) {
-                const int kn = kc + nw;
-                const bool more = kn < p.NC;  // uniform over the wavefront
-                if (more) load_chunk(nxt, kn);
-                compute(cur);
-                if (!more) break;
-                cur = nxt;
-                kc = kn;
+    // ---- stream this wavefront's chunks kc = wave, wave + nw, ...; PF chunks of loads stay in
+    //      flight ahead of the multiply.  The ring of PF + 1 register buffers is indexed at
+    //      compile time, so the steady-state loop is unrolled by PF + 1; inside it every load is
+    //      unconditional, which lets the compiler wait for exactly the chunk it multiplies. ----
+    const int n_my = (p.NC - wave + nw - 1) / nw;  // chunks this wavefront owns (NC >= nw, so >= 1)
+    auto kc_of = [&](int i) { return wave + i * nw; };
+    chunk_t buf[PF + 1];
+
+    if constexpr (XLDS) {
+        // Copy this token block's x into LDS in fragment order: fragment f = g * tc + row holds
+        // x[tok0 + row][g * LANE_K .. + LANE_K), zero beyond d_model.  The first group of x loads
+        // is issued before the first W loads and, hitting L2, returns before them.
+        constexpr int XG = 4;  // fragments per thread per group
+        const int nthr = blockDim.x;
+        auto x_load = [&](int f) {
+            const int fc = min(f, x_frags - 1);  // clamped: the load is always in bounds
+            const int row = fc % tc, g = fc / tc;
+            const long k0 = min((long)g * Tr::LANE_K, (long)p.h - Tr::LANE_K);
+            return *reinterpret_cast<const frag *>(static_cast<const char *>(p.x) +
+                                                   ((long)(tok0 + row) * p.h + k0) * Tr::ELEM_BYTES);
+        };
+        auto x_store = [&](int f, frag v) {
+            if (f < x_frags) {
+                if ((long)(f / tc) * Tr::LANE_K >= p.h) v = frag{0, 0, 0, 0};
+                lds_x[f] = v;
             }
+        };
+        frag xv[XG];
+#pragma unroll
+        for (int b = 0; b < XG; ++b) xv[b] = x_load(threadIdx.x + b * nthr);
+#pragma unroll
+        for (int s = 0; s < PF; ++s) load_chunk(buf[s], kc_of(min(s, n_my - 1)));
+#pragma unroll
+        for (int b = 0; b < XG; ++b) x_store(threadIdx.x + b * nthr, xv[b]);
+        for (int f0 = threadIdx.x + XG * nthr; f0 < x_frags; f0 += XG * nthr) {
+#pragma unroll
+            for (int b = 0; b < XG; ++b) xv[b] = x_load(f0 + b * nthr);
+#pragma unroll
+            for (int b = 0; b < XG; ++b) x_store(f0 + b * nthr, xv[b]);
         }
+        __syncthreads();
+    } else {
+#pragma unroll
+        for (int s = 0; s < PF; ++s) load_chunk(buf[s], kc_of(min(s, n_my - 1)));
+    }
+
+    int i0 = 0;
+    for (; i0 + 2 * PF < n_my; i0 += PF + 1) {  // every stage of the group has a chunk left to load
+#pragma unroll
+        for (int s = 0; s <= PF; ++s) {
+            load_chunk(buf[(s + PF) % (PF + 1)], kc_of(i0 + s + PF));
+            compute(buf[s], kc_of(i0 + s));
+        }
+    }
+    // tail: at most 2 PF chunks; i0 is a multiple of PF + 1, so chunk i0 + s sits in buf[s % (PF + 1)]
+#pragma unroll
+    for (int s = 0; s < 2 * PF; ++s) {
+        const int i = i0 + s;
+        if (i >= n_my) break;  // uniform over the wavefront
+        if (i + PF < n_my) load_chunk(buf[(s + PF) % (PF + 1)], kc_of(i + PF));
+        compute(buf[s % (PF + 1)], kc_of(i));
     }
 
     // ---- combine the K split: wavefronts 1..nw-1 hand their sums to wavefront 0 through LDS,
     //      which adds them in wavefront order (fixed order => reproducible bits) -------------
-    const int tc = (TB == 1) ? min(p.T - tok0, 16) : 16;  // token lanes that carry data
     if (nw > 1) {
         if (wave > 0 && r < tc) {
 #pragma unroll
             for (int s = 0; s < SETS; ++s)
 #pragma unroll
                 for (int tb = 0; tb < TB; ++tb)
-                    lds[(((wave - 1) * SETS + s) * TB + tb) * (4 * tc) + q * tc + r] = acc[s][tb];
+                    lds_red[(((wave - 1) * SETS + s) * TB + tb) * (4 * tc) + q * tc + r] = acc[s][tb];
         }
         __syncthreads();
         if (wave == 0 && r < tc) {
@@ -163,7 +245,7 @@ __global__ __launch_bounds__(512) void stream_kernel(StreamParams p)
                 for (int s = 0; s < SETS; ++s)
 #pragma unroll
                     for (int tb = 0; tb < TB; ++tb)
-                        acc[s][tb] += lds[(((w - 1) * SETS + s) * TB + tb) * (4 * tc) + q * tc + r];
+                        acc[s][tb] += lds_red[(((w - 1) * SETS + s) * TB + tb) * (4 * tc) + q * tc + r];
         }
     }
     if (wave != 0) return;
@@ -222,42 +304,47 @@ __global__ __launch_bounds__(512) void stream_kernel(StreamParams p)
 
 // ---- host side --------------------------------------------------------------------------------
 
-template <typename Tr, int NMP, int TB, int MODE>
-static hipError_t launch_one(const StreamParams &p, int nw, size_t lds_bytes, dim3 grid, hipStream_t stream)
+struct StreamLaunch {
+    int tb;         // token blocks (of 16) per workgroup
+    int nw;         // wavefronts per workgroup = K-split ways
+    bool xlds;      // x staged in LDS
+    size_t lds;     // dynamic LDS bytes
+    dim3 grid;
+};
+
+template <typename Tr, int NMP, int TB, int MODE, bool XLDS>
+static hipError_t launch_one(const StreamParams &p, const StreamLaunch &l, hipStream_t stream)
 {
-    auto kern = stream_kernel<Tr, NMP, TB, MODE>;
-    if (lds_bytes > 48 * 1024) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
-        if (e != hipSuccess) return e;
-    }
-    hipLaunchKernelGGL(kern, grid, dim3(nw * kWave), lds_bytes, stream, p);
+    constexpr int PF = XLDS ? MGLU_STREAM_PREFETCH_XLDS : 1;
+    auto kern = stream_kernel<Tr, NMP, TB, MODE, XLDS, PF>;
+    hipLaunchKernelGGL(kern, l.grid, dim3(l.nw * kWave), l.lds, stream, p);
     return hipGetLastError();
 }
 
 template <typename Tr, int NMP, int MODE>
-static hipError_t launch_tb(const StreamParams &p, int tb, int nw, size_t lds, dim3 grid, hipStream_t s)
+static hipError_t launch_tb(const StreamParams &p, const StreamLaunch &l, hipStream_t s)
 {
     // token blocks per workgroup are bounded by the 256-register budget: see stream_max_token_blocks
     constexpr bool kIsBf16 = Tr::ELEM_BYTES == 2;
-    if (tb == 1) return launch_one<Tr, NMP, 1, MODE>(p, nw, lds, grid, s);
+    if (l.tb == 1)
+        return l.xlds ? launch_one<Tr, NMP, 1, MODE, true>(p, l, s) : launch_one<Tr, NMP, 1, MODE, false>(p, l, s);
     if constexpr (kIsBf16) {
-        if (tb == 2) return launch_one<Tr, NMP, 2, MODE>(p, nw, lds, grid, s);
+        if (l.tb == 2) return launch_one<Tr, NMP, 2, MODE, false>(p, l, s);
         if constexpr (NMP <= 2) {
-            if (tb == 4) return launch_one<Tr, NMP, 4, MODE>(p, nw, lds, grid, s);
+            if (l.tb == 4) return launch_one<Tr, NMP, 4, MODE, false>(p, l, s);
         }
     }
     return hipErrorInvalidValue;
 }
 
 template <typename Tr, int MODE>
-static hipError_t launch_nmp(const StreamParams &p, int nmp, int tb, int nw, size_t lds, dim3 grid, hipStream_t s)
+static hipError_t launch_nmp(const StreamParams &p, int nmp, const StreamLaunch &l, hipStream_t s)
 {
     switch (nmp) {
-    case 1: return launch_tb<Tr, 1, MODE>(p, tb, nw, lds, grid, s);
-    case 2: return launch_tb<Tr, 2, MODE>(p, tb, nw, lds, grid, s);
-    case 4: return launch_tb<Tr, 4, MODE>(p, tb, nw, lds, grid, s);
-    default: return launch_tb<Tr, 8, MODE>(p, tb, nw, lds, grid, s);
+    case 1: return launch_tb<Tr, 1, MODE>(p, l, s);
+    case 2: return launch_tb<Tr, 2, MODE>(p, l, s);
+    case 4: return launch_tb<Tr, 4, MODE>(p, l, s);
+    default: return launch_tb<Tr, 8, MODE>(p, l, s);
     }
 }
 
@@ -270,27 +357,35 @@ hipError_t launch_stream(const StreamParams &p, bool is_f32, int mode, hipStream
     const int sets = (mode == kModeSwiglu) ? 2 : 1 + nmp;
     const int max_tb = stream_max_token_blocks(nmp, is_f32);
     const int blocks = (int)ceil_div(p.T, 16);
-    const int tb = (blocks >= 4 && max_tb >= 4) ? 4 : (blocks >= 2 && max_tb >= 2) ? 2 : 1;
-    const int tc = (tb == 1) ? (p.T < 16 ? p.T : 16) : 16;
+    const int elem = is_f32 ? 4 : 2;
+    constexpr size_t kLdsBudget = 64 * 1024;
 
-    // wavefronts per workgroup: as many as there are chunks, at most 8, and the LDS hand-over must fit
-    int nw = p.NC < 8 ? p.NC : 8;
-    auto lds_bytes = [&](int n) { return (size_t)(n - 1) * sets * tb * 4 * tc * sizeof(f32x4); };
-    while (nw > 1 && lds_bytes(nw) > 64 * 1024) nw >>= 1;
-    const size_t lds = nw > 1 ? lds_bytes(nw) : 0;
+    StreamLaunch l;
+    l.tb = (blocks >= 4 && max_tb >= 4) ? 4 : (blocks >= 2 && max_tb >= 2) ? 2 : 1;
+    const int tc = (l.tb == 1) ? (p.T < 16 ? p.T : 16) : 16;
 
-    dim3 grid(p.NB, (unsigned)ceil_div(p.T, 16 * tb));
+    // wavefronts per workgroup: as many as there are chunks, at most MGLU_STREAM_MAX_WAVES,
+    // and the LDS hand-over area must fit
+    l.nw = p.NC < MGLU_STREAM_MAX_WAVES ? p.NC : MGLU_STREAM_MAX_WAVES;
+    auto red_bytes = [&](int n) { return n > 1 ? (size_t)(n - 1) * sets * l.tb * 4 * tc * sizeof(f32x4) : (size_t)0; };
+    while (l.nw > 1 && red_bytes(l.nw) > kLdsBudget) l.nw >>= 1;
+
+    const size_t x_bytes = (size_t)p.NC * kChunkK * tc * elem;
+    l.xlds = (l.tb == 1) && (x_bytes + red_bytes(l.nw) <= kLdsBudget);
+    l.lds = red_bytes(l.nw) + (l.xlds ? x_bytes : 0);
+    l.grid = dim3(p.NB, (unsigned)ceil_div(p.T, 16 * l.tb));
+
     if (is_f32) {
         switch (mode) {
-        case kModeMglu: return launch_nmp<F32Traits, kModeMglu>(p, nmp, tb, nw, lds, grid, stream);
-        case kModeProjections: return launch_nmp<F32Traits, kModeProjections>(p, nmp, tb, nw, lds, grid, stream);
-        default: return launch_tb<F32Traits, 1, kModeSwiglu>(p, tb, nw, lds, grid, stream);
+        case kModeMglu: return launch_nmp<F32Traits, kModeMglu>(p, nmp, l, stream);
+        case kModeProjections: return launch_nmp<F32Traits, kModeProjections>(p, nmp, l, stream);
+        default: return launch_tb<F32Traits, 1, kModeSwiglu>(p, l, stream);
         }
     }
     switch (mode) {
-    case kModeMglu: return launch_nmp<Bf16Traits, kModeMglu>(p, nmp, tb, nw, lds, grid, stream);
-    case kModeProjections: return launch_nmp<Bf16Traits, kModeProjections>(p, nmp, tb, nw, lds, grid, stream);
-    default: return launch_tb<Bf16Traits, 1, kModeSwiglu>(p, tb, nw, lds, grid, stream);
+    case kModeMglu: return launch_nmp<Bf16Traits, kModeMglu>(p, nmp, l, stream);
+    case kModeProjections: return launch_nmp<Bf16Traits, kModeProjections>(p, nmp, l, stream);
+    default: return launch_tb<Bf16Traits, 1, kModeSwiglu>(p, l, stream);
     }
 }
 
