@@ -83,6 +83,22 @@ mglu::StreamParams stream_params(const mglu_desc *d)
     return p;
 }
 
+// Token counts above this go to the MFMA-tiled prefill kernel (bf16); at or below it the
+// layer is bound by streaming W and runs on the streaming kernel.
+constexpr int kStreamMaxTokens = 64;
+
+mglu::PrefillParams prefill_params(const mglu_desc *d)
+{
+    mglu::PrefillParams p = {};
+    p.T = d->tokens;
+    p.h = d->d_model;
+    p.d = d->d_ff;
+    p.n_masks = d->n_masks;
+    p.NB = (int)mglu::ceil_div(d->d_ff, mglu::kColBlock);
+    p.NC = (int)mglu::ceil_div(d->d_model, mglu::kChunkK);
+    return p;
+}
+
 mglu::PackParams pack_params(const mglu_desc *d, const void *src, void *dst)
 {
     mglu::PackParams p = {};
@@ -160,6 +176,15 @@ mglu_status mglu_forward(const mglu_desc *desc, const void *x_dev, const void *W
     MGLU_TRY(check_ptr(out_dev, "out_dev"));
     (void)workspace_dev;
     (void)workspace_bytes;
+    if (desc->dtype == MGLU_BF16 && desc->tokens > kStreamMaxTokens) {
+        mglu::PrefillParams pp = prefill_params(desc);
+        pp.x = x_dev;
+        pp.w = W_packed_dev;
+        pp.m = static_cast<const uint32_t *>(masks_packed_dev);
+        pp.out = out_dev;
+        return hip_result(mglu::launch_prefill(pp, mglu::kModeMglu, static_cast<hipStream_t>(stream)),
+                          "mglu_forward (prefill) launch");
+    }
     mglu::StreamParams p = stream_params(desc);
     p.x = x_dev;
     p.w = W_packed_dev;
@@ -230,6 +255,15 @@ mglu_status swiglu_forward(const mglu_desc *desc, const void *x_dev, const void 
     MGLU_TRY(check_ptr(out_dev, "out_dev"));
     (void)workspace_dev;
     (void)workspace_bytes;
+    if (desc->dtype == MGLU_BF16 && desc->tokens > kStreamMaxTokens) {
+        mglu::PrefillParams pp = prefill_params(desc);
+        pp.x = x_dev;
+        pp.w = Wg_packed_dev;
+        pp.w2 = Wv_packed_dev;
+        pp.out = out_dev;
+        return hip_result(mglu::launch_prefill(pp, mglu::kModeSwiglu, static_cast<hipStream_t>(stream)),
+                          "swiglu_forward (prefill) launch");
+    }
     mglu::StreamParams p = stream_params(desc);
     p.x = x_dev;
     p.w = Wg_packed_dev;

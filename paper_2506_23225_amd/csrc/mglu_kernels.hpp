@@ -19,6 +19,18 @@ struct StreamParams {
     int NC;               // reduction chunks = ceil(h / 128)
 };
 
+struct PrefillParams {
+    const void *x;        // [T][h] bf16
+    const void *w;        // packed weights (SwiGLU: the gate matrix)
+    const void *w2;       // SwiGLU only: packed value matrix
+    const uint32_t *m;    // packed masks
+    void *out;            // [T][d] bf16
+    int T, h, d, n_masks;
+    int NB, NC;
+    int tiles_m, tiles_n; // filled in by the launcher
+    int group_m;          // token tiles per L2 patch
+};
+
 struct PackParams {
     const void *src;      // W or mask bytes, layout per `nk`
     void *dst;
@@ -30,6 +42,8 @@ struct PackParams {
 hipError_t launch_stream(const StreamParams &p, bool is_f32, int mode, hipStream_t stream);
 int stream_max_token_blocks(int nmp, bool is_f32);
 hipError_t launch_stream_read(const void *buf, size_t bytes, uint32_t *sink, hipStream_t stream);
+
+hipError_t launch_prefill(const PrefillParams &p, int mode, hipStream_t stream);
 
 hipError_t launch_pack_weights(const PackParams &p, bool is_f32, hipStream_t stream);
 hipError_t launch_pack_masks(const PackParams &p, bool is_f32, hipStream_t stream);

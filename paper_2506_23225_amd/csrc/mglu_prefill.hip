@@ -1,0 +1,286 @@
+// MFMA-tiled MGLU kernel for prefill / large batches (bf16): compute-bound.
+//
+// The paper has no batched kernel; what it states for this regime is the cost model
+// (Discussion, "Computational Cost": one dense contraction plus one per mask).  The layer
+// is Eq. 3; the complement trick of Alg. 1 carries over: per output tile the kernel keeps
+// 1 + n_m accumulator sets, t = x W and dsum_i = x (W with the sign of every gate element
+// flipped), and the epilogue forms gate_i = (t - dsum_i)/2, value_i = (t + dsum_i)/2,
+// sum_i swish(gate_i) * value_i in registers.  So the matrix cores do (1 + n_m) GEMMs'
+// worth of work instead of the 2 n_m of the naive form, and W, the masks and x are each
+// staged once per tile for all of them.
+//
+// Tiling (one workgroup = 8 wavefronts = one CU at 2 wavefronts per SIMD):
+//   workgroup tile  BM = 16*TB tokens  x  BN = 8*16*CB columns
+//   wavefront w owns CB column blocks of 16 columns, for all BM tokens
+//   A operand (W): streamed straight from global memory in the packed tile order -- each
+//     wavefront reads only its own column blocks, so LDS staging would buy no reuse
+//   masks: read next to W, one chunk (128 k) of words at a time, applied in registers
+//   B operand (x): shared by all 8 wavefronts -> staged through LDS in B-fragment order,
+//     double-buffered per 128-k chunk, one barrier per chunk
+//   MFMA: v_mfma_f32_16x16x32_bf16, 16 columns x 16 tokens per accumulator
+// Workgroup ids are remapped so that the workgroups resident on one XCD (ids equal mod 8)
+// cover a compact patch of tiles and share W / x through that XCD's L2.
+#include <type_traits>
+
+#include "mglu_common.hpp"
+#include "mglu_kernels.hpp"
+
+namespace mglu {
+
+constexpr int kPrefillWaves = 8;
+
+template <int NMP, int CB, int TB, int MODE>
+__global__ __launch_bounds__(kPrefillWaves *kWave) void prefill_kernel(PrefillParams p)
+{
+    typedef Bf16Traits Tr;
+    typedef Tr::frag frag;
+    constexpr int SETS = (MODE == kModeSwiglu) ? 2 : 1 + NMP;
+    constexpr int AD = 2;                       // A-fragment prefetch distance in tiles
+    constexpr int AR = 4;                       // ring entries (one per tile of a chunk)
+    constexpr long CHUNK_BYTES = (long)kColBlock * kChunkK * 2;
+    constexpr int XPIECES = TB * 4 / kPrefillWaves;  // x fragments each wavefront stages per chunk
+    static_assert(TB * 4 % kPrefillWaves == 0, "token blocks must split evenly over the wavefronts");
+    extern __shared__ f32x4 lds_raw[];
+    frag *lds_x = reinterpret_cast<frag *>(lds_raw);   // [2][tile t<4][tb<TB][lane<64]
+
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    const int r = lane & 15, q = lane >> 4;
+
+    // ---- XCD-aware tile order: ids equal mod 8 share an L2; give each XCD a band of column
+    //      tiles and walk it in patches of p.group_m token tiles ----
+    int tile_m, tile_n;
+    {
+        const int wg = blockIdx.x;
+        const int xcd = wg & 7, local = wg >> 3;
+        const int per_xcd = (p.tiles_n + 7) >> 3;         // column tiles per XCD band
+        const int gm = p.group_m;
+        const int patch = local / (gm * per_xcd);          // which group of token tiles
+        const int in_patch = local - patch * gm * per_xcd;
+        const int m0 = patch * gm;
+        const int rows = min(gm, p.tiles_m - m0);          // last patch may be short
+        tile_m = m0 + in_patch % rows;
+        tile_n = xcd * per_xcd + in_patch / rows;
+        if (tile_m >= p.tiles_m || tile_n >= p.tiles_n || in_patch / rows >= per_xcd) return;
+    }
+    const int tok0 = tile_m * (16 * TB);
+    const int jb0 = (tile_n * kPrefillWaves + wave) * CB;   // first column block of this wavefront
+
+    // column blocks past the end are clamped for the loads and dropped at the store
+    const char *wbase[CB];
+    const char *w2base[CB];
+    const uint32_t *mbase[CB];
+#pragma unroll
+    for (int cb = 0; cb < CB; ++cb) {
+        const long jb = min(jb0 + cb, p.NB - 1);
+        wbase[cb] = static_cast<const char *>(p.w) + jb * p.NC * CHUNK_BYTES + lane * 16;
+        w2base[cb] = static_cast<const char *>(p.w2) + jb * p.NC * CHUNK_BYTES + lane * 16;
+        mbase[cb] = p.m + (jb * p.NC * kWave + lane) * NMP;
+    }
+
+    f32x4 acc[SETS][CB][TB];
+#pragma unroll
+    for (int s = 0; s < SETS; ++s)
+#pragma unroll
+        for (int cb = 0; cb < CB; ++cb)
+#pragma unroll
+            for (int tb = 0; tb < TB; ++tb) acc[s][cb][tb] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    // ---- x staging: wavefront w copies fragments idx = w + 8 s (idx = tb * 4 + t) of a chunk:
+    //      lane (r, q) moves x[tok0 + 16 tb + r][128 kc + 32 t + 8 q .. + 8) to LDS slot
+    //      (t * TB + tb) * 64 + lane, the order the B operand is read in ----
+    auto x_src = [&](int kc, int s) {
+        const int idx = wave + kPrefillWaves * s;
+        const int tb = idx >> 2, t = idx & 3;
+        const long tok = min((long)tok0 + 16 * tb + r, (long)p.T - 1);
+        const long k0 = min((long)kc * kChunkK + 32 * t + 8 * q, (long)p.h - 8);
+        return reinterpret_cast<const frag *>(static_cast<const char *>(p.x) + (tok * p.h + k0) * 2);
+    };
+    auto x_dst = [&](int buf, int s) {
+        const int idx = wave + kPrefillWaves * s;
+        const int tb = idx >> 2, t = idx & 3;
+        return lds_x + ((buf * 4 + t) * TB + tb) * kWave + lane;
+    };
+    auto x_valid = [&](int kc, int s) {
+        const int idx = wave + kPrefillWaves * s;
+        const int t = idx & 3;
+        return kc * kChunkK + 32 * t + 8 * q < p.h;   // beyond d_model: zero (W is zero-padded there too)
+    };
+
+    // ---- A ring: entry t holds the fragments of tile t of the current (or next) chunk ----
+    frag aw[AR][CB];
+    frag aw2[MODE == kModeSwiglu ? AR : 1][CB];
+    uint32_t mk[2][CB][NMP];   // mask words of the current and the next chunk
+
+    auto load_a = [&](int kc, int t, int slot) {
+#pragma unroll
+        for (int cb = 0; cb < CB; ++cb) {
+            aw[slot][cb] = *reinterpret_cast<const frag *>(wbase[cb] + (long)kc * CHUNK_BYTES + t * 1024);
+            if constexpr (MODE == kModeSwiglu)
+                aw2[slot][cb] = *reinterpret_cast<const frag *>(w2base[cb] + (long)kc * CHUNK_BYTES + t * 1024);
+        }
+    };
+    auto load_masks = [&](int kc, int slot) {
+        if constexpr (MODE != kModeSwiglu) {
+#pragma unroll
+            for (int cb = 0; cb < CB; ++cb) {
+                const uint32_t *mp = mbase[cb] + (long)kc * kWave * NMP;
+                if constexpr (NMP == 8) {
+                    u32x4 a = *reinterpret_cast<const u32x4 *>(mp), b = *(reinterpret_cast<const u32x4 *>(mp) + 1);
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) { mk[slot][cb][i] = a[i]; mk[slot][cb][4 + i] = b[i]; }
+                } else if constexpr (NMP == 4) {
+                    u32x4 a = *reinterpret_cast<const u32x4 *>(mp);
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) mk[slot][cb][i] = a[i];
+                } else if constexpr (NMP == 2) {
+                    u32x2 a = *reinterpret_cast<const u32x2 *>(mp);
+                    mk[slot][cb][0] = a.x; mk[slot][cb][1] = a.y;
+                } else {
+                    mk[slot][cb][0] = *mp;
+                }
+            }
+        }
+    };
+
+    // ---- prologue: stage chunk 0 of x, start the A ring and the masks ----
+    const int last = p.NC - 1;
+    {
+        frag xv[XPIECES];
+#pragma unroll
+        for (int s = 0; s < XPIECES; ++s) xv[s] = *x_src(0, s);
+        load_masks(0, 0);
+#pragma unroll
+        for (int t = 0; t < AD; ++t) load_a(0, t, t);
+#pragma unroll
+        for (int s = 0; s < XPIECES; ++s) *x_dst(0, s) = x_valid(0, s) ? xv[s] : frag{0, 0, 0, 0};
+    }
+    __syncthreads();
+
+    // One chunk of the K loop; MS = which half of mk[] holds this chunk's masks (compile time).
+    auto chunk_step = [&](int kc, auto ms_tag) {
+        constexpr int MS = decltype(ms_tag)::value;
+        const int buf = kc & 1;
+        const int kn = min(kc + 1, last);   // next chunk, clamped: its loads are then always in bounds
+        load_masks(kn, MS ^ 1);
+        frag xv[XPIECES];
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            // prefetch the A fragments AD tiles ahead and one piece of the next chunk's x
+            if (t + AD < 4) load_a(kc, t + AD, (t + AD) % AR);
+            else load_a(kn, t + AD - 4, (t + AD) % AR);
+#pragma unroll
+            for (int s = 0; s < XPIECES; ++s)
+                if (s % 4 == t) xv[s] = *x_src(kn, s);
+
+            // operand variants of this tile: W itself and W with mask i's gate elements negated
+            frag var[SETS][CB];
+#pragma unroll
+            for (int cb = 0; cb < CB; ++cb) {
+                var[0][cb] = aw[t][cb];
+                if constexpr (MODE == kModeSwiglu) {
+                    var[1][cb] = aw2[t][cb];
+                } else {
+#pragma unroll
+                    for (int i = 0; i < NMP; ++i) var[1 + i][cb] = Tr::template flip<NMP>(aw[t][cb], mk[MS][cb], t, i);
+                }
+            }
+            const frag *xb = lds_x + ((buf * 4 + t) * TB) * kWave + lane;
+#pragma unroll
+            for (int tb = 0; tb < TB; ++tb) {
+                const frag b = xb[tb * kWave];
+#pragma unroll
+                for (int s = 0; s < SETS; ++s)
+#pragma unroll
+                    for (int cb = 0; cb < CB; ++cb) acc[s][cb][tb] = Tr::mma(var[s][cb], b, acc[s][cb][tb]);
+            }
+#pragma unroll
+            for (int s = 0; s < XPIECES; ++s)
+                if (s % 4 == t) *x_dst(buf ^ 1, s) = x_valid(kn, s) ? xv[s] : frag{0, 0, 0, 0};
+        }
+        __syncthreads();
+    };
+
+    int kc = 0;
+    for (; kc + 1 < p.NC; kc += 2) {
+        chunk_step(kc, std::integral_constant<int, 0>{});
+        chunk_step(kc + 1, std::integral_constant<int, 1>{});
+    }
+    if (kc < p.NC) chunk_step(kc, std::integral_constant<int, 0>{});
+
+    // ---- epilogue (Eq. 3): lane (r, q) holds token 16 tb + r, columns 4 q .. 4 q + 3 of each block ----
+#pragma unroll
+    for (int cb = 0; cb < CB; ++cb) {
+        const int jb = jb0 + cb;
+        if (jb >= p.NB) continue;
+        const int j0 = jb * kColBlock + 4 * q;
+        if (j0 >= p.d) continue;
+        const bool full = (j0 + 3 < p.d) && ((p.d & 3) == 0);
+#pragma unroll
+        for (int tb = 0; tb < TB; ++tb) {
+            const long tok = (long)tok0 + 16 * tb + r;
+            if (tok >= p.T) continue;
+            f32x4 y;
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                if constexpr (MODE == kModeSwiglu) {
+                    y[c] = swish(acc[0][cb][tb][c]) * acc[1][cb][tb][c];
+                } else {
+                    const float t = acc[0][cb][tb][c];
+                    float sum = 0.f;
+#pragma unroll
+                    for (int i = 0; i < NMP; ++i) {
+                        if (i >= p.n_masks) break;
+                        const float ds = acc[1 + i][cb][tb][c];
+                        sum += swish(gate_of(t, ds)) * value_of(t, ds);
+                    }
+                    y[c] = sum;
+                }
+            }
+            const long o = tok * p.d + j0;
+            if (full) {
+                Tr::store4(p.out, o, y);
+            } else {
+#pragma unroll
+                for (int c = 0; c < 4; ++c)
+                    if (j0 + c < p.d) Tr::store1(p.out, o + c, y[c]);
+            }
+        }
+    }
+}
+
+// ---- host side --------------------------------------------------------------------------------
+
+template <int NMP, int CB, int TB, int MODE>
+static hipError_t launch_prefill_one(PrefillParams p, hipStream_t stream)
+{
+    const int bm = 16 * TB, bn = kPrefillWaves * kColBlock * CB;
+    p.tiles_m = (int)ceil_div(p.T, bm);
+    p.tiles_n = (int)ceil_div(p.d, bn);
+    p.group_m = p.tiles_m < 8 ? p.tiles_m : 8;
+    // every XCD gets per_xcd column tiles x tiles_m token tiles; ids beyond a band's end return at once
+    const int per_xcd = (p.tiles_n + 7) / 8;
+    const long wgs = (long)8 * per_xcd * p.tiles_m;
+    const size_t lds = (size_t)2 * 4 * TB * kWave * sizeof(f32x4);
+    auto kern = prefill_kernel<NMP, CB, TB, MODE>;
+    if (lds > 48 * 1024) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+    }
+    hipLaunchKernelGGL(kern, dim3((unsigned)wgs), dim3(kPrefillWaves * kWave), lds, stream, p);
+    return hipGetLastError();
+}
+
+hipError_t launch_prefill(const PrefillParams &p, int mode, hipStream_t stream)
+{
+    if (mode == kModeSwiglu) return launch_prefill_one<1, 2, 8, kModeSwiglu>(p, stream);
+    switch (round_up_masks(p.n_masks)) {
+    case 1: return launch_prefill_one<1, 2, 8, kModeMglu>(p, stream);
+    case 2: return launch_prefill_one<2, 1, 8, kModeMglu>(p, stream);
+    case 4: return launch_prefill_one<4, 1, 8, kModeMglu>(p, stream);
+    default: return launch_prefill_one<8, 1, 4, kModeMglu>(p, stream);
+    }
+}
+
+}  // namespace mglu

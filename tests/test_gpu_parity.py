@@ -55,6 +55,16 @@ def test_ragged_shapes(dtype, T, h, d, n_m):
     _check_full(x, W, masks, _run(x, W, masks))
 
 
+@pytest.mark.parametrize("T,h,d,n_m", [
+    (65, 128, 16, 1), (128, 256, 128, 4), (200, 520, 272, 4), (300, 384, 1000, 8), (129, 1024, 130, 2),
+    (257, 136, 2064, 1), (1100, 256, 300, 3), (96, 2048, 144, 8),
+])
+def test_prefill_kernel_ragged_shapes(T, h, d, n_m):
+    """Token counts above 64 take the MFMA-tiled kernel: ragged token, column and reduction tails."""
+    x, W, masks = synth.make_inputs(h, d, n_m, T, dtype="bf16", seed=T + h + d, device=DEV)
+    _check_full(x, W, masks, _run(x, W, masks))
+
+
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
 def test_nk_layout_and_bool_entry(dtype):
     x, W, masks = synth.make_inputs(392, 72, 3, 4, dtype=dtype, seed=5, device=DEV)
@@ -82,7 +92,15 @@ def test_decode_8b_config_sampled(T):
     print("decode_8b T=%d rel err" % T, _check_columns(x, W, masks, out, edge_columns(cfg["d_ff"])))
 
 
-@pytest.mark.parametrize("n_m,T", [(1, 1), (2, 32), (4, 1), (8, 32)])
+def test_prefill_8b_config_sampled():
+    """Full-size prefill configuration: all 4096 tokens on sampled columns (tile edges, tail, random)."""
+    cfg = synth.config("prefill_8b")
+    x, W, masks = synth.make_inputs(**cfg, seed=0, device=DEV)
+    out = _run(x, W, masks)
+    print("prefill_8b rel err", _check_columns(x, W, masks, out, edge_columns(cfg["d_ff"], n_random=48)))
+
+
+@pytest.mark.parametrize("n_m,T", [(1, 1), (2, 32), (4, 1), (8, 32), (1, 2048), (8, 2048)])
 def test_large_config_sampled(n_m, T):
     cfg = synth.config("large", n_masks=n_m, tokens=T)
     x, W, masks = synth.make_inputs(**cfg, seed=0, device=DEV)
@@ -140,7 +158,7 @@ def test_rows_independent_and_mask_order_and_determinism():
     assert rel_err(to_np64(perm), to_np64(full)) <= 1e-2       # fp32 sum order differs, value does not
 
 
-@pytest.mark.parametrize("dtype,T", [("bf16", 1), ("bf16", 16), ("f32", 3)])
+@pytest.mark.parametrize("dtype,T", [("bf16", 1), ("bf16", 16), ("f32", 3), ("bf16", 150)])
 def test_swiglu_reference_kernel(dtype, T):
     xg, Wg, _ = synth.make_inputs(768, 208, 1, T, dtype=dtype, seed=6, device=DEV)
     _, Wv, _ = synth.make_inputs(768, 208, 1, T, dtype=dtype, seed=7, device=DEV)
