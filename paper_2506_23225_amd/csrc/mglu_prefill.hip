@@ -25,17 +25,26 @@
 #include "mglu_common.hpp"
 #include "mglu_kernels.hpp"
 
+// Tile shapes per mask count, chosen so that the accumulators plus the operand ring stay
+// inside the 256 registers a wavefront has at 2 wavefronts per SIMD (no scratch).
+#ifndef MGLU_PREFILL_AD4
+#define MGLU_PREFILL_AD4 2
+#endif
+#ifndef MGLU_PREFILL_TB4
+#define MGLU_PREFILL_TB4 6   // token blocks per workgroup tile for four masks
+#endif
+
 namespace mglu {
 
 constexpr int kPrefillWaves = 8;
 
-template <int NMP, int CB, int TB, int MODE>
+// AD: how many tiles ahead of the multiply the A fragments are fetched.
+template <int NMP, int CB, int TB, int MODE, int AD>
 __global__ __launch_bounds__(kPrefillWaves *kWave) void prefill_kernel(PrefillParams p)
 {
     typedef Bf16Traits Tr;
     typedef Tr::frag frag;
     constexpr int SETS = (MODE == kModeSwiglu) ? 2 : 1 + NMP;
-    constexpr int AD = 2;                       // A-fragment prefetch distance in tiles
     constexpr int AR = 4;                       // ring entries (one per tile of a chunk)
     constexpr long CHUNK_BYTES = (long)kColBlock * kChunkK * 2;
     constexpr int XPIECES = TB * 4 / kPrefillWaves;  // x fragments each wavefront stages per chunk
@@ -162,16 +171,20 @@ __global__ __launch_bounds__(kPrefillWaves *kWave) void prefill_kernel(PrefillPa
         constexpr int MS = decltype(ms_tag)::value;
         const int buf = kc & 1;
         const int kn = min(kc + 1, last);   // next chunk, clamped: its loads are then always in bounds
-        load_masks(kn, MS ^ 1);
         frag xv[XPIECES];
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
-            // prefetch the A fragments AD tiles ahead and one piece of the next chunk's x
-            if (t + AD < 4) load_a(kc, t + AD, (t + AD) % AR);
-            else load_a(kn, t + AD - 4, (t + AD) % AR);
+            // Issue this tile's prefetches first: pieces of the next chunk's x (stored one tile
+            // later), the A fragments AD tiles ahead, and once per chunk the next chunk's masks.
+            // The scheduling fence keeps the compiler from sinking these loads down to their
+            // first use, which would expose the whole memory latency.
 #pragma unroll
             for (int s = 0; s < XPIECES; ++s)
-                if (s % 4 == t) xv[s] = *x_src(kn, s);
+                if (s * 3 / XPIECES == t) xv[s] = *x_src(kn, s);
+            if (t + AD < 4) load_a(kc, t + AD, (t + AD) % AR);
+            else load_a(kn, t + AD - 4, (t + AD) % AR);
+            if (t == 0) load_masks(kn, MS ^ 1);
+            __builtin_amdgcn_sched_barrier(0);
 
             // operand variants of this tile: W itself and W with mask i's gate elements negated
             frag var[SETS][CB];
@@ -195,8 +208,8 @@ __global__ __launch_bounds__(kPrefillWaves *kWave) void prefill_kernel(PrefillPa
                     for (int cb = 0; cb < CB; ++cb) acc[s][cb][tb] = Tr::mma(var[s][cb], b, acc[s][cb][tb]);
             }
 #pragma unroll
-            for (int s = 0; s < XPIECES; ++s)
-                if (s % 4 == t) *x_dst(buf ^ 1, s) = x_valid(kn, s) ? xv[s] : frag{0, 0, 0, 0};
+            for (int s = 0; s < XPIECES; ++s)   // a piece is stored one tile after its load was issued
+                if (s * 3 / XPIECES + 1 == t) *x_dst(buf ^ 1, s) = x_valid(kn, s) ? xv[s] : frag{0, 0, 0, 0};
         }
         __syncthreads();
     };
@@ -251,7 +264,7 @@ __global__ __launch_bounds__(kPrefillWaves *kWave) void prefill_kernel(PrefillPa
 
 // ---- host side --------------------------------------------------------------------------------
 
-template <int NMP, int CB, int TB, int MODE>
+template <int NMP, int CB, int TB, int MODE, int AD>
 static hipError_t launch_prefill_one(PrefillParams p, hipStream_t stream)
 {
     const int bm = 16 * TB, bn = kPrefillWaves * kColBlock * CB;
@@ -262,7 +275,7 @@ static hipError_t launch_prefill_one(PrefillParams p, hipStream_t stream)
     const int per_xcd = (p.tiles_n + 7) / 8;
     const long wgs = (long)8 * per_xcd * p.tiles_m;
     const size_t lds = (size_t)2 * 4 * TB * kWave * sizeof(f32x4);
-    auto kern = prefill_kernel<NMP, CB, TB, MODE>;
+    auto kern = prefill_kernel<NMP, CB, TB, MODE, AD>;
     if (lds > 48 * 1024) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
@@ -274,12 +287,12 @@ static hipError_t launch_prefill_one(PrefillParams p, hipStream_t stream)
 
 hipError_t launch_prefill(const PrefillParams &p, int mode, hipStream_t stream)
 {
-    if (mode == kModeSwiglu) return launch_prefill_one<1, 2, 8, kModeSwiglu>(p, stream);
+    if (mode == kModeSwiglu) return launch_prefill_one<1, 2, 8, kModeSwiglu, 1>(p, stream);
     switch (round_up_masks(p.n_masks)) {
-    case 1: return launch_prefill_one<1, 2, 8, kModeMglu>(p, stream);
-    case 2: return launch_prefill_one<2, 1, 8, kModeMglu>(p, stream);
-    case 4: return launch_prefill_one<4, 1, 8, kModeMglu>(p, stream);
-    default: return launch_prefill_one<8, 1, 4, kModeMglu>(p, stream);
+    case 1: return launch_prefill_one<1, 2, 8, kModeMglu, 1>(p, stream);
+    case 2: return launch_prefill_one<2, 1, 8, kModeMglu, 2>(p, stream);
+    case 4: return launch_prefill_one<4, 1, MGLU_PREFILL_TB4, kModeMglu, MGLU_PREFILL_AD4>(p, stream);
+    default: return launch_prefill_one<8, 1, 4, kModeMglu, 2>(p, stream);
     }
 }
 
