@@ -22,6 +22,7 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0        # MI355X HBM3E, published
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16, published
 LLC_BYTES = 256 * 2 ** 20    # last-level (Infinity) cache
+HEADLINE = "decode_gemv 2048x5632 n_m=4 T=1"
 
 
 def parse_args():
@@ -31,6 +32,12 @@ def parse_args():
     ap.add_argument("--warmup", type=int, default=200)
     ap.add_argument("--no-extra", action="store_true", help="headline workload only")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
+    ap.add_argument("--no-refs", action="store_true",
+                    help="skip the warm-cache, SwiGLU-reference and read-ceiling legs of the headline")
+    ap.add_argument("--probe", default="",
+                    help="profiling aid: launch only this workload ('headline' or a substring of an extra "
+                         "workload's name) 20 times, then one mglu_stream_read and one device copy of "
+                         "exactly 1 GiB each (known sizes to scale byte counters by), print nothing")
     ap.add_argument("--only", default="", help="comma list of extra workloads to run (names as printed)")
     return ap.parse_args()
 
@@ -143,42 +150,45 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
 
+    if args.probe:
+        return probe(torch, synth, args)
+
     # ---- headline: decode GEMV, cold ring ----
     head_cfg = synth.config("decode_gemv")
-    head = Workload("decode_gemv 2048x5632 n_m=4 T=1", head_cfg)
+    head = Workload(HEADLINE, head_cfg, swiglu=not args.no_refs)
     ms, wall_ms = time_steps(torch, head.step, args.steps, args.warmup)
     rec = summarize(head, ms, wall_ms, "hbm")
-    sw_ms, _ = time_steps(torch, head.swiglu_step, args.steps, args.warmup)
-    warm = Workload("decode_gemv warm", head_cfg, ring_bytes=1, swiglu=False)
-    warm_ms, _ = time_steps(torch, warm.step, args.steps, args.warmup)
-
-    # measured streaming-read ceiling of this GPU (same load pattern, nothing else)
-    buf = torch.empty(2 ** 30, dtype=torch.uint8, device="cuda:0").random_(0, 255)
-    sink = torch.zeros(256, dtype=torch.int32, device="cuda:0")
-    read_ms, _ = time_steps(torch, lambda i: api.mglu_stream_read(buf, sink), 50, 5)
-    read_gbs = buf.numel() / read_ms / 1e6
-    del buf
 
     result = {
         "metric": "MGLU decode HBM GB/s (frac of peak) + prefill TFLOP/s, tokens/s per layer",
         "value": rec["GBps"], "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": head.name, "d_model": 2048, "d_ff": 5632, "n_masks": 4, "tokens": 1,
+        "config": {"workload": HEADLINE, "d_model": 2048, "d_ff": 5632, "n_masks": 4, "tokens": 1,
                    "ring_copies": head.copies, "cache": "cold (ring of copies > 2x last-level cache)"},
         "tokens_per_s": rec["tokens_per_s"], "hbm_frac": rec["hbm_frac"],
         "wall_ms_per_step": wall_ms,
-        "warm_cache": {"ms": warm_ms, "GBps": head.bytes / warm_ms / 1e6},
-        "swiglu_reference": {"ms": sw_ms, "GBps": head.glu_bytes / sw_ms / 1e6,
-                             "mglu_over_swiglu_time": ms / sw_ms,
-                             "byte_model_ratio": (16 + head_cfg["n_masks"]) / 32.0},
-        "measured_read_ceiling_GBps": read_gbs,
         "roofline": {"bound": "hbm", "achieved": rec["GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": rec["hbm_frac"], "traffic": None,
-                     "kernel": "mglu::stream_kernel<Bf16Traits,4,1,0>",
+                     "frac": rec["hbm_frac"], "traffic": measured_traffic("decode_gemv"),
+                     "kernel": "mglu::stream_kernel<mglu::Bf16Traits, 4, 1, 0, true, 1>",
                      "bytes_per_launch": head.bytes},
     }
-    del head, warm
+    if not args.no_refs:
+        sw_ms, _ = time_steps(torch, head.swiglu_step, args.steps, args.warmup)
+        warm = Workload("decode_gemv warm", head_cfg, ring_bytes=1, swiglu=False)
+        warm_ms, _ = time_steps(torch, warm.step, args.steps, args.warmup)
+        del warm
+        # measured streaming-read ceiling of this GPU (same load pattern, nothing else)
+        buf = torch.empty(2 ** 30, dtype=torch.uint8, device="cuda:0").random_(0, 255)
+        sink = torch.zeros(256, dtype=torch.int32, device="cuda:0")
+        read_ms, _ = time_steps(torch, lambda i: api.mglu_stream_read(buf, sink), 50, 5)
+        del buf
+        result["warm_cache"] = {"ms": warm_ms, "GBps": head.bytes / warm_ms / 1e6}
+        result["swiglu_reference"] = {"ms": sw_ms, "GBps": head.glu_bytes / sw_ms / 1e6,
+                                      "mglu_over_swiglu_time": ms / sw_ms,
+                                      "byte_model_ratio": (16 + head_cfg["n_masks"]) / 32.0}
+        result["measured_read_ceiling_GBps"] = 2 ** 30 / read_ms / 1e6
+    del head
 
     if not args.no_extra:
         result["extra"] = run_extras(torch, synth, args)
@@ -188,12 +198,20 @@ def main():
     print(json.dumps(result))
 
 
-def rec_bytes(cfg):
-    from paper_2506_23225_amd import costmodel
-    return costmodel.mglu_bytes(cfg["d_model"], cfg["d_ff"], cfg["n_masks"], cfg["tokens"], cfg["dtype"])
+def measured_traffic(key):
+    """HBM bytes per launch from the committed rocprofv3 counter summary (profiles/traffic.txt), or None."""
+    path = os.path.join(ROOT, "profiles", "traffic.txt")
+    if not os.path.exists(path):
+        return None
+    with open(path) as f:
+        for line in f:
+            parts = line.split()
+            if len(parts) >= 2 and parts[0] == key:
+                return float(parts[1])
+    return None
 
 
-def run_extras(torch, synth, args):
+def extra_cases(synth):
     cases = []
     for T in (1, 4, 16):
         cases.append(("decode_8b 4096x14336 n_m=8 T=%d" % T, synth.config("decode_8b", tokens=T), "hbm", 200, 20))
@@ -205,6 +223,37 @@ def run_extras(torch, synth, args):
     for n_m in (1, 2, 4, 8):
         cases.append(("large 8192x28672 n_m=%d T=2048" % n_m,
                       synth.config("large", n_masks=n_m, tokens=2048), "mfma", 5, 1))
+    return cases
+
+
+def probe(torch, synth, args):
+    """For rocprofv3 counter runs: 20 launches of one workload, then two kernels of known size (1 GiB):
+    the library's streaming read, which issues the same 16-byte-per-lane loads as the MGLU kernels
+    (read counters), and a plain device copy (write counters)."""
+    if args.probe == "headline":
+        name, cfg = HEADLINE, synth.config("decode_gemv")
+    else:
+        name, cfg = next((n, c) for n, c, _, _, _ in extra_cases(synth) if args.probe in n)
+    w = Workload(name, cfg, swiglu=False)
+    for i in range(20):
+        w.step(i)
+    from paper_2506_23225_amd import api
+    src = torch.empty(2 ** 30, dtype=torch.uint8, device="cuda:0")
+    dst = torch.empty_like(src)
+    sink = torch.zeros(256, dtype=torch.int32, device="cuda:0")
+    torch.cuda.synchronize()
+    api.mglu_stream_read(src, sink)
+    dst.copy_(src)
+    torch.cuda.synchronize()
+
+
+def rec_bytes(cfg):
+    from paper_2506_23225_amd import costmodel
+    return costmodel.mglu_bytes(cfg["d_model"], cfg["d_ff"], cfg["n_masks"], cfg["tokens"], cfg["dtype"])
+
+
+def run_extras(torch, synth, args):
+    cases = extra_cases(synth)
     only = [s.strip() for s in args.only.split(",") if s.strip()]
     out = []
     for name, cfg, bound, steps, warmup in cases:

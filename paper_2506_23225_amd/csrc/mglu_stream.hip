@@ -32,6 +32,9 @@
 #ifndef MGLU_STREAM_PREFETCH_XLDS
 #define MGLU_STREAM_PREFETCH_XLDS 1  // chunks of loads in flight per wavefront when x sits in LDS
 #endif
+#ifndef MGLU_STREAM_NONTEMPORAL
+#define MGLU_STREAM_NONTEMPORAL 1  // W and the masks are read once per call: mark the loads streaming
+#endif
 #if MGLU_STREAM_WAVES_PER_EU
 #define MGLU_STREAM_OCCUPANCY __attribute__((amdgpu_waves_per_eu(MGLU_STREAM_WAVES_PER_EU, MGLU_STREAM_WAVES_PER_EU)))
 #else
@@ -39,6 +42,16 @@
 #endif
 
 namespace mglu {
+
+template <typename T>
+__device__ inline T stream_load(const T *p)
+{
+#if MGLU_STREAM_NONTEMPORAL
+    return __builtin_nontemporal_load(p);
+#else
+    return *p;
+#endif
+}
 
 // Registers of one chunk in flight: W (or the two SwiGLU matrices), the mask words and, when x
 // is not staged in LDS, the x fragments.
@@ -100,28 +113,28 @@ __global__ __launch_bounds__(512) MGLU_STREAM_OCCUPANCY void stream_kernel(Strea
         const char *wp = wbase + (long)kc * CHUNK_BYTES;
 #pragma unroll
         for (int t = 0; t < Tr::TILES; ++t)
-            c.w[t] = __builtin_nontemporal_load(reinterpret_cast<const frag *>(wp + t * 1024));
+            c.w[t] = stream_load(reinterpret_cast<const frag *>(wp + t * 1024));
         if constexpr (MODE == kModeSwiglu) {
             const char *wp2 = w2base + (long)kc * CHUNK_BYTES;
 #pragma unroll
             for (int t = 0; t < Tr::TILES; ++t)
-                c.w2[t] = __builtin_nontemporal_load(reinterpret_cast<const frag *>(wp2 + t * 1024));
+                c.w2[t] = stream_load(reinterpret_cast<const frag *>(wp2 + t * 1024));
         } else {
             const uint32_t *mp = mbase + (long)kc * kWave * NMP;
             if constexpr (NMP == 8) {
-                u32x4 a = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(mp));
-                u32x4 b = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(mp) + 1);
+                u32x4 a = stream_load(reinterpret_cast<const u32x4 *>(mp));
+                u32x4 b = stream_load(reinterpret_cast<const u32x4 *>(mp) + 1);
 #pragma unroll
                 for (int i = 0; i < 4; ++i) { c.m[i] = a[i]; c.m[4 + i] = b[i]; }
             } else if constexpr (NMP == 4) {
-                u32x4 a = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(mp));
+                u32x4 a = stream_load(reinterpret_cast<const u32x4 *>(mp));
 #pragma unroll
                 for (int i = 0; i < 4; ++i) c.m[i] = a[i];
             } else if constexpr (NMP == 2) {
-                u32x2 a = __builtin_nontemporal_load(reinterpret_cast<const u32x2 *>(mp));
+                u32x2 a = stream_load(reinterpret_cast<const u32x2 *>(mp));
                 c.m[0] = a.x; c.m[1] = a.y;
             } else {
-                c.m[0] = __builtin_nontemporal_load(mp);
+                c.m[0] = stream_load(mp);
             }
         }
         if constexpr (!XLDS) {
