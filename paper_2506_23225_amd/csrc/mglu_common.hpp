@@ -42,10 +42,10 @@ __host__ __device__ constexpr int round_up_masks(int n) { return n <= 1 ? 1 : n 
 __host__ __device__ constexpr long ceil_div(long a, long b) { return (a + b - 1) / b; }
 
 // ---- fp32 <-> bf16 ---------------------------------------------------------------------
-__device__ inline float bf16_bits_to_f32(uint32_t b) { return __uint_as_float(b << 16); }
+__device__ __forceinline__ float bf16_bits_to_f32(uint32_t b) { return __uint_as_float(b << 16); }
 
 // round to nearest, ties to even; NaN stays NaN
-__device__ inline uint32_t f32_to_bf16_bits(float f)
+__device__ __forceinline__ uint32_t f32_to_bf16_bits(float f)
 {
     uint32_t u = __float_as_uint(f);
     if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x40u;
@@ -54,7 +54,7 @@ __device__ inline uint32_t f32_to_bf16_bits(float f)
 }
 
 // ---- Swish, beta = 1:  z * sigmoid(z) = z / (1 + exp(-z)) --------------------------------
-__device__ inline float swish(float z)
+__device__ __forceinline__ float swish(float z)
 {
     // exp(-z) overflows to +inf for z < -88 and the quotient is then -0, the right limit.
     return __fdividef(z, 1.0f + __expf(-z));
@@ -69,7 +69,7 @@ struct Bf16Traits {
     static constexpr int LANE_K = 8;          // consecutive k one lane holds per tile
     static constexpr int ELEM_BYTES = 2;
 
-    __device__ static inline f32x4 mma(frag a, frag b, f32x4 c)
+    __device__ static __forceinline__ f32x4 mma(frag a, frag b, f32x4 c)
     {
         return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a),
                                                        __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
@@ -77,7 +77,7 @@ struct Bf16Traits {
 
     // W fragment of tile t with the sign of every element whose bit in mask i is set flipped.
     template <int NMP>
-    __device__ static inline frag flip(frag w, const uint32_t (&m)[NMP], int t, int i)
+    __device__ static __forceinline__ frag flip(frag w, const uint32_t (&m)[NMP], int t, int i)
     {
         frag r;
 #pragma unroll
@@ -88,14 +88,14 @@ struct Bf16Traits {
         return r;
     }
 
-    __device__ static inline void store4(void *out, long idx, f32x4 v)
+    __device__ static __forceinline__ void store4(void *out, long idx, f32x4 v)
     {
         u32x2 pk;
         pk.x = f32_to_bf16_bits(v.x) | (f32_to_bf16_bits(v.y) << 16);
         pk.y = f32_to_bf16_bits(v.z) | (f32_to_bf16_bits(v.w) << 16);
         *reinterpret_cast<u32x2 *>(static_cast<uint16_t *>(out) + idx) = pk;
     }
-    __device__ static inline void store1(void *out, long idx, float v)
+    __device__ static __forceinline__ void store1(void *out, long idx, float v)
     {
         static_cast<uint16_t *>(out)[idx] = (uint16_t)f32_to_bf16_bits(v);
     }
@@ -108,7 +108,7 @@ struct F32Traits {
     static constexpr int LANE_K = 4;
     static constexpr int ELEM_BYTES = 4;
 
-    __device__ static inline f32x4 mma(frag a, frag b, f32x4 c)
+    __device__ static __forceinline__ f32x4 mma(frag a, frag b, f32x4 c)
     {
 #pragma unroll
         for (int e = 0; e < 4; ++e) c = __builtin_amdgcn_mfma_f32_16x16x4f32(a[e], b[e], c, 0, 0, 0);
@@ -116,7 +116,7 @@ struct F32Traits {
     }
 
     template <int NMP>
-    __device__ static inline frag flip(frag w, const uint32_t (&m)[NMP], int t, int i)
+    __device__ static __forceinline__ frag flip(frag w, const uint32_t (&m)[NMP], int t, int i)
     {
         frag r;
 #pragma unroll
@@ -127,11 +127,11 @@ struct F32Traits {
         return r;
     }
 
-    __device__ static inline void store4(void *out, long idx, f32x4 v)
+    __device__ static __forceinline__ void store4(void *out, long idx, f32x4 v)
     {
         *reinterpret_cast<f32x4 *>(static_cast<float *>(out) + idx) = v;
     }
-    __device__ static inline void store1(void *out, long idx, float v) { static_cast<float *>(out)[idx] = v; }
+    __device__ static __forceinline__ void store1(void *out, long idx, float v) { static_cast<float *>(out)[idx] = v; }
 };
 
 // ---- what a launch computes ---------------------------------------------------------------
@@ -144,9 +144,10 @@ enum Mode {
 // Sign-flip form of the complement trick (Alg. 1 writes s_i and t - s_i): with
 // t = sum v and dsum_i = sum (1 - 2 M_i) v over the same terms in the same order,
 //   gate_i = (t - dsum_i) / 2,   value_i = (t + dsum_i) / 2.
-// An all-gate mask gives dsum_i = -t bit for bit (rounding is sign-symmetric), hence
-// value_i = 0 exactly; an all-value mask gives gate_i = 0 exactly.
-__device__ inline float gate_of(float t, float dsum) { return 0.5f * (t - dsum); }
-__device__ inline float value_of(float t, float dsum) { return 0.5f * (t + dsum); }
+// An all-value mask leaves W untouched, so dsum_i = t bit for bit and gate_i = 0 exactly.
+// An all-gate mask gives dsum_i = -t only up to the last bit (the matrix cores' accumulation
+// is not exactly sign-symmetric), so value_i is then a few ulp of t instead of exactly 0.
+__device__ __forceinline__ float gate_of(float t, float dsum) { return 0.5f * (t - dsum); }
+__device__ __forceinline__ float value_of(float t, float dsum) { return 0.5f * (t + dsum); }
 
 }  // namespace mglu

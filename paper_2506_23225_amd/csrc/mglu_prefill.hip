@@ -276,11 +276,6 @@ static hipError_t launch_prefill_one(PrefillParams p, hipStream_t stream)
     const long wgs = (long)8 * per_xcd * p.tiles_m;
     const size_t lds = (size_t)2 * 4 * TB * kWave * sizeof(f32x4);
     auto kern = prefill_kernel<NMP, CB, TB, MODE, AD>;
-    if (lds > 48 * 1024) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return e;
-    }
     hipLaunchKernelGGL(kern, dim3((unsigned)wgs), dim3(kPrefillWaves * kWave), lds, stream, p);
     return hipGetLastError();
 }

@@ -1,4 +1,4 @@
-// Streaming MGLU kernel for decode and small batches (tokens <= 64): HBM-bound.
+// Streaming MGLU kernels for decode and small batches (tokens <= 64): HBM-bound.
 //
 // Paper: section "FlashMGLU", Alg. 1 (split-K matrix-vector product with packed
 // masks).  Kept from it: W and the packed mask words are read once, the unmasked
@@ -15,36 +15,47 @@
 //   - Swish, the gate*value products and the sum over masks are applied to the
 //     reduced sums in registers and only `out` is written (Eq. 3).
 //
-// Work split: workgroup (jb, tg) owns output columns [16 jb, 16 jb + 16) for the
-// token group tg of 16*TB tokens; its wavefronts take the chunks kc = wave, wave +
-// nw, ... of that column block, so at any moment the workgroup reads one contiguous
-// run of the packed weight stream.
+// Two kernels share the chunk loader, the tile multiply and the epilogue:
+//   stream_resident_kernel  up to 16 tokens whose rows of x fit in LDS: x is copied there
+//                           once, in B-operand order; no barrier inside the K loop.
+//   stream_panel_kernel     any token count up to 64: a workgroup owns NWC column blocks, its
+//                           wavefronts (NWC x NWK) share panels of x (NWK chunks of K) staged
+//                           through double-buffered LDS, one barrier per panel, so x is
+//                           fetched once per NWC * 16 columns instead of once per 16.
+// In both, a wavefront's chunks of one column block are interleaved with those of the other
+// wavefronts that split K with it, so together they read one contiguous run of the packed
+// weight stream at any moment.
+#include <type_traits>
+
 #include "mglu_common.hpp"
 #include "mglu_kernels.hpp"
 
 // Tuning knobs (compile-time; the defaults are the measured best on MI355X).
 #ifndef MGLU_STREAM_MAX_WAVES
-#define MGLU_STREAM_MAX_WAVES 4   // wavefronts per workgroup = ways the reduction dimension is split
+#define MGLU_STREAM_MAX_WAVES 4   // resident kernel: wavefronts per workgroup = K-split ways
 #endif
-#ifndef MGLU_STREAM_WAVES_PER_EU
-#define MGLU_STREAM_WAVES_PER_EU 0  // 0: let the compiler pick the register budget
-#endif
-#ifndef MGLU_STREAM_PREFETCH_XLDS
-#define MGLU_STREAM_PREFETCH_XLDS 1  // chunks of loads in flight per wavefront when x sits in LDS
+#ifndef MGLU_STREAM_PREFETCH
+#define MGLU_STREAM_PREFETCH 1    // chunks of loads in flight per wavefront ahead of the multiply
 #endif
 #ifndef MGLU_STREAM_NONTEMPORAL
-#define MGLU_STREAM_NONTEMPORAL 1  // W and the masks are read once per call: mark the loads streaming
+#define MGLU_STREAM_NONTEMPORAL 1 // W and the masks are read once per call: mark the loads streaming
 #endif
-#if MGLU_STREAM_WAVES_PER_EU
-#define MGLU_STREAM_OCCUPANCY __attribute__((amdgpu_waves_per_eu(MGLU_STREAM_WAVES_PER_EU, MGLU_STREAM_WAVES_PER_EU)))
-#else
-#define MGLU_STREAM_OCCUPANCY
+// Panel kernel workgroup shapes (column blocks x K-split ways x chunks per wavefront per panel):
+// "wide" shares each x panel among 8 column blocks and needs d_ff / 128 workgroups to fill the
+// chip; "split" halves the columns and splits K instead, for narrower layers.
+#ifndef MGLU_PANEL_WIDE_MIN_WGS
+#define MGLU_PANEL_WIDE_MIN_WGS 200
 #endif
+
+// Register budget of the panel kernel: always at least 2 wavefronts per SIMD (256 registers);
+// instantiations with many accumulators (more than 12 sets x token blocks) are told to aim
+// for exactly 2, or the compiler spills them down to 128 registers in pursuit of occupancy.
+#define MGLU_PANEL_OCCUPANCY(SETS_X_TB) __attribute__((amdgpu_waves_per_eu(2, (SETS_X_TB) > 12 ? 2 : 8)))
 
 namespace mglu {
 
 template <typename T>
-__device__ inline T stream_load(const T *p)
+__device__ __forceinline__ T stream_load(const T *p)
 {
 #if MGLU_STREAM_NONTEMPORAL
     return __builtin_nontemporal_load(p);
@@ -53,224 +64,76 @@ __device__ inline T stream_load(const T *p)
 #endif
 }
 
-// Registers of one chunk in flight: W (or the two SwiGLU matrices), the mask words and, when x
-// is not staged in LDS, the x fragments.
-template <typename Tr, int NMP, int TB, int MODE, bool XLDS>
-struct Chunk {
+__host__ __device__ constexpr int sets_of(int mode, int nmp) { return mode == kModeSwiglu ? 2 : 1 + nmp; }
+
+// Registers of one chunk in flight: W (or the two SwiGLU matrices) and the mask words.
+template <typename Tr, int NMP, int MODE>
+struct WChunk {
     typename Tr::frag w[Tr::TILES];
     typename Tr::frag w2[MODE == kModeSwiglu ? Tr::TILES : 1];
     uint32_t m[NMP];
-    typename Tr::frag x[XLDS ? 1 : TB][XLDS ? 1 : Tr::TILES];
 };
 
-// XLDS: the token block's rows of x are copied once into LDS in B-operand order and read from
-//       there tile by tile (needs TB == 1 and tokens * d_model small enough); otherwise every
-//       chunk loads its x fragments from global memory (L2 hits) next to W.
-// PF:   chunks of loads in flight ahead of the one being multiplied.
-template <typename Tr, int NMP, int TB, int MODE, bool XLDS, int PF>
-__global__ __launch_bounds__(512) MGLU_STREAM_OCCUPANCY void stream_kernel(StreamParams p)
+// wp / wp2 / mp already point at this lane's place in the chunk.
+template <typename Tr, int NMP, int MODE>
+__device__ __forceinline__ void load_wchunk(WChunk<Tr, NMP, MODE> &c, const char *wp, const char *wp2, const uint32_t *mp)
 {
-    static_assert(!XLDS || TB == 1, "x is staged in LDS for a single token block only");
-    constexpr int SETS = (MODE == kModeSwiglu) ? 2 : 1 + NMP;
-    constexpr long CHUNK_BYTES = (long)kColBlock * kChunkK * Tr::ELEM_BYTES;
     typedef typename Tr::frag frag;
-    typedef Chunk<Tr, NMP, TB, MODE, XLDS> chunk_t;
-    extern __shared__ f32x4 lds[];
-
-    const int lane = threadIdx.x & 63;
-    const int wave = threadIdx.x >> 6;
-    const int nw = blockDim.x >> 6;
-    const int r = lane & 15, q = lane >> 4;
-    const int jb = blockIdx.x;
-    const int tok0 = blockIdx.y * (16 * TB);
-    const int tc = (TB == 1) ? min(p.T - tok0, 16) : 16;  // token lanes that carry data
-
-    const char *wbase = static_cast<const char *>(p.w) + (long)jb * p.NC * CHUNK_BYTES + lane * 16;
-    const char *w2base = static_cast<const char *>(p.w2) + (long)jb * p.NC * CHUNK_BYTES + lane * 16;
-    const uint32_t *mbase = p.m + ((long)jb * p.NC * kWave + lane) * NMP;
-
-    bool tok_ok[TB];
-    const char *xrow[TB];
 #pragma unroll
-    for (int tb = 0; tb < TB; ++tb) {
-        const int tok = tok0 + 16 * tb + r;
-        tok_ok[tb] = tok < p.T;
-        xrow[tb] = static_cast<const char *>(p.x) + (long)(tok_ok[tb] ? tok : 0) * p.h * Tr::ELEM_BYTES;
+    for (int t = 0; t < Tr::TILES; ++t) c.w[t] = stream_load(reinterpret_cast<const frag *>(wp + t * 1024));
+    if constexpr (MODE == kModeSwiglu) {
+#pragma unroll
+        for (int t = 0; t < Tr::TILES; ++t) c.w2[t] = stream_load(reinterpret_cast<const frag *>(wp2 + t * 1024));
+    } else if constexpr (NMP == 8) {
+        u32x4 a = stream_load(reinterpret_cast<const u32x4 *>(mp));
+        u32x4 b = stream_load(reinterpret_cast<const u32x4 *>(mp) + 1);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) { c.m[i] = a[i]; c.m[4 + i] = b[i]; }
+    } else if constexpr (NMP == 4) {
+        u32x4 a = stream_load(reinterpret_cast<const u32x4 *>(mp));
+#pragma unroll
+        for (int i = 0; i < 4; ++i) c.m[i] = a[i];
+    } else if constexpr (NMP == 2) {
+        u32x2 a = stream_load(reinterpret_cast<const u32x2 *>(mp));
+        c.m[0] = a.x; c.m[1] = a.y;
+    } else {
+        c.m[0] = stream_load(mp);
     }
+}
 
-    // LDS: [x fragments of this token block, XLDS only][hand-over area of the K-split reduction]
-    frag *lds_x = reinterpret_cast<frag *>(lds);
-    const int x_frags = XLDS ? p.NC * Tr::TILES * 4 * tc : 0;
-    f32x4 *lds_red = lds + x_frags;
-
-    f32x4 acc[SETS][TB];
+// One 32-k (bf16) / 16-k (fp32) tile: t += W x, dsum_i += flip_i(W) x for every token block.
+template <typename Tr, int NMP, int TB, int MODE>
+__device__ __forceinline__ void mma_tile(f32x4 (&acc)[sets_of(MODE, NMP)][TB], const WChunk<Tr, NMP, MODE> &c, int t,
+                                const typename Tr::frag (&xf)[TB])
+{
 #pragma unroll
-    for (int s = 0; s < SETS; ++s)
+    for (int tb = 0; tb < TB; ++tb) acc[0][tb] = Tr::mma(c.w[t], xf[tb], acc[0][tb]);
+    if constexpr (MODE == kModeSwiglu) {
 #pragma unroll
-        for (int tb = 0; tb < TB; ++tb) acc[s][tb] = f32x4{0.f, 0.f, 0.f, 0.f};
-
-    auto load_chunk = [&](chunk_t &c, int kc) {
-        const char *wp = wbase + (long)kc * CHUNK_BYTES;
-#pragma unroll
-        for (int t = 0; t < Tr::TILES; ++t)
-            c.w[t] = stream_load(reinterpret_cast<const frag *>(wp + t * 1024));
-        if constexpr (MODE == kModeSwiglu) {
-            const char *wp2 = w2base + (long)kc * CHUNK_BYTES;
-#pragma unroll
-            for (int t = 0; t < Tr::TILES; ++t)
-                c.w2[t] = stream_load(reinterpret_cast<const frag *>(wp2 + t * 1024));
-        } else {
-            const uint32_t *mp = mbase + (long)kc * kWave * NMP;
-            if constexpr (NMP == 8) {
-                u32x4 a = stream_load(reinterpret_cast<const u32x4 *>(mp));
-                u32x4 b = stream_load(reinterpret_cast<const u32x4 *>(mp) + 1);
-#pragma unroll
-                for (int i = 0; i < 4; ++i) { c.m[i] = a[i]; c.m[4 + i] = b[i]; }
-            } else if constexpr (NMP == 4) {
-                u32x4 a = stream_load(reinterpret_cast<const u32x4 *>(mp));
-#pragma unroll
-                for (int i = 0; i < 4; ++i) c.m[i] = a[i];
-            } else if constexpr (NMP == 2) {
-                u32x2 a = stream_load(reinterpret_cast<const u32x2 *>(mp));
-                c.m[0] = a.x; c.m[1] = a.y;
-            } else {
-                c.m[0] = stream_load(mp);
-            }
-        }
-        if constexpr (!XLDS) {
-#pragma unroll
-            for (int tb = 0; tb < TB; ++tb)
-#pragma unroll
-                for (int t = 0; t < Tr::TILES; ++t) {
-                    const int k0 = kc * kChunkK + t * Tr::TILE_K + q * Tr::LANE_K;
-                    frag v = frag{0, 0, 0, 0};
-                    if (tok_ok[tb] && k0 < p.h)
-                        v = *reinterpret_cast<const frag *>(xrow[tb] + (long)k0 * Tr::ELEM_BYTES);
-                    c.x[tb][t] = v;
-                }
-        }
-    };
-
-    auto compute = [&](const chunk_t &c, int kc) {
-#pragma unroll
-        for (int t = 0; t < Tr::TILES; ++t) {
-            frag xf[TB];
-            if constexpr (XLDS) {
-                xf[0] = frag{0, 0, 0, 0};
-                if (r < tc) xf[0] = lds_x[((kc * Tr::TILES + t) * 4 + q) * tc + r];
-            } else {
-#pragma unroll
-                for (int tb = 0; tb < TB; ++tb) xf[tb] = c.x[tb][t];
-            }
-#pragma unroll
-            for (int tb = 0; tb < TB; ++tb) acc[0][tb] = Tr::mma(c.w[t], xf[tb], acc[0][tb]);
-            if constexpr (MODE == kModeSwiglu) {
-#pragma unroll
-                for (int tb = 0; tb < TB; ++tb) acc[1][tb] = Tr::mma(c.w2[t], xf[tb], acc[1][tb]);
-            } else {
-#pragma unroll
-                for (int i = 0; i < NMP; ++i) {
-                    const frag wf = Tr::template flip<NMP>(c.w[t], c.m, t, i);
-#pragma unroll
-                    for (int tb = 0; tb < TB; ++tb) acc[1 + i][tb] = Tr::mma(wf, xf[tb], acc[1 + i][tb]);
-                }
-            }
-        }
-    };
-
-    // ---- stream this wavefront's chunks kc = wave, wave + nw, ...; PF chunks of loads stay in
-    //      flight ahead of the multiply.  The ring of PF + 1 register buffers is indexed at
-    //      compile time, so the steady-state loop is unrolled by PF + 1; inside it every load is
-    //      unconditional, which lets the compiler wait for exactly the chunk it multiplies. ----
-    const int n_my = (p.NC - wave + nw - 1) / nw;  // chunks this wavefront owns (NC >= nw, so >= 1)
-    auto kc_of = [&](int i) { return wave + i * nw; };
-    chunk_t buf[PF + 1];
-
-    if constexpr (XLDS) {
-        // Copy this token block's x into LDS in fragment order: fragment f = g * tc + row holds
-        // x[tok0 + row][g * LANE_K .. + LANE_K), zero beyond d_model.  The first group of x loads
-        // is issued before the first W loads and, hitting L2, returns before them.
-        constexpr int XG = 4;  // fragments per thread per group
-        const int nthr = blockDim.x;
-        auto x_load = [&](int f) {
-            const int fc = min(f, x_frags - 1);  // clamped: the load is always in bounds
-            const int row = fc % tc, g = fc / tc;
-            const long k0 = min((long)g * Tr::LANE_K, (long)p.h - Tr::LANE_K);
-            return *reinterpret_cast<const frag *>(static_cast<const char *>(p.x) +
-                                                   ((long)(tok0 + row) * p.h + k0) * Tr::ELEM_BYTES);
-        };
-        auto x_store = [&](int f, frag v) {
-            if (f < x_frags) {
-                if ((long)(f / tc) * Tr::LANE_K >= p.h) v = frag{0, 0, 0, 0};
-                lds_x[f] = v;
-            }
-        };
-        frag xv[XG];
-#pragma unroll
-        for (int b = 0; b < XG; ++b) xv[b] = x_load(threadIdx.x + b * nthr);
-#pragma unroll
-        for (int s = 0; s < PF; ++s) load_chunk(buf[s], kc_of(min(s, n_my - 1)));
-#pragma unroll
-        for (int b = 0; b < XG; ++b) x_store(threadIdx.x + b * nthr, xv[b]);
-        for (int f0 = threadIdx.x + XG * nthr; f0 < x_frags; f0 += XG * nthr) {
-#pragma unroll
-            for (int b = 0; b < XG; ++b) xv[b] = x_load(f0 + b * nthr);
-#pragma unroll
-            for (int b = 0; b < XG; ++b) x_store(f0 + b * nthr, xv[b]);
-        }
-        __syncthreads();
+        for (int tb = 0; tb < TB; ++tb) acc[1][tb] = Tr::mma(c.w2[t], xf[tb], acc[1][tb]);
     } else {
 #pragma unroll
-        for (int s = 0; s < PF; ++s) load_chunk(buf[s], kc_of(min(s, n_my - 1)));
-    }
-
-    int i0 = 0;
-    for (; i0 + 2 * PF < n_my; i0 += PF + 1) {  // every stage of the group has a chunk left to load
+        for (int i = 0; i < NMP; ++i) {
+            const typename Tr::frag wf = Tr::template flip<NMP>(c.w[t], c.m, t, i);
 #pragma unroll
-        for (int s = 0; s <= PF; ++s) {
-            load_chunk(buf[(s + PF) % (PF + 1)], kc_of(i0 + s + PF));
-            compute(buf[s], kc_of(i0 + s));
+            for (int tb = 0; tb < TB; ++tb) acc[1 + i][tb] = Tr::mma(wf, xf[tb], acc[1 + i][tb]);
         }
     }
-    // tail: at most 2 PF chunks; i0 is a multiple of PF + 1, so chunk i0 + s sits in buf[s % (PF + 1)]
-#pragma unroll
-    for (int s = 0; s < 2 * PF; ++s) {
-        const int i = i0 + s;
-        if (i >= n_my) break;  // uniform over the wavefront
-        if (i + PF < n_my) load_chunk(buf[(s + PF) % (PF + 1)], kc_of(i + PF));
-        compute(buf[s % (PF + 1)], kc_of(i));
-    }
+}
 
-    // ---- combine the K split: wavefronts 1..nw-1 hand their sums to wavefront 0 through LDS,
-    //      which adds them in wavefront order (fixed order => reproducible bits) -------------
-    if (nw > 1) {
-        if (wave > 0 && r < tc) {
-#pragma unroll
-            for (int s = 0; s < SETS; ++s)
-#pragma unroll
-                for (int tb = 0; tb < TB; ++tb)
-                    lds_red[(((wave - 1) * SETS + s) * TB + tb) * (4 * tc) + q * tc + r] = acc[s][tb];
-        }
-        __syncthreads();
-        if (wave == 0 && r < tc) {
-            for (int w = 1; w < nw; ++w)
-#pragma unroll
-                for (int s = 0; s < SETS; ++s)
-#pragma unroll
-                    for (int tb = 0; tb < TB; ++tb)
-                        acc[s][tb] += lds_red[(((w - 1) * SETS + s) * TB + tb) * (4 * tc) + q * tc + r];
-        }
-    }
-    if (wave != 0) return;
-
-    // ---- epilogue on the reduced sums (Eq. 3): lane (r, q) holds token r, columns 4q..4q+3 ----
+// Epilogue on the reduced sums (Eq. 3): lane (r, q) holds token 16 tb + r, columns 4q .. 4q+3 of block jb.
+template <typename Tr, int NMP, int TB, int MODE>
+__device__ __forceinline__ void epilogue(const StreamParams &p, const f32x4 (&acc)[sets_of(MODE, NMP)][TB], int jb, int tok0,
+                                int r, int q)
+{
     const int j0 = jb * kColBlock + 4 * q;
+    if (j0 >= p.d) return;
+    const bool full = (j0 + 3 < p.d) && ((p.d & 3) == 0);
 #pragma unroll
     for (int tb = 0; tb < TB; ++tb) {
-        if (!tok_ok[tb] || j0 >= p.d) continue;
-        const long tok = tok0 + 16 * tb + r;
+        const long tok = (long)tok0 + 16 * tb + r;
+        if (tok >= p.T) continue;
         const long o = tok * p.d + j0;
-        const bool full = (j0 + 3 < p.d) && ((p.d & 3) == 0);
         if constexpr (MODE == kModeProjections) {
             const long plane = (long)p.T * p.d;
 #pragma unroll
@@ -315,90 +178,388 @@ __global__ __launch_bounds__(512) MGLU_STREAM_OCCUPANCY void stream_kernel(Strea
     }
 }
 
+// ================================================================================================
+// Resident kernel: workgroup (jb, tg) owns columns [16 jb, 16 jb + 16) for the token block tg of
+// up to 16 tokens; its nw wavefronts take chunks kc = wave, wave + nw, ...
+// ================================================================================================
+template <typename Tr, int NMP, int MODE, int PF>
+__global__ __launch_bounds__(512) void stream_resident_kernel(StreamParams p)
+{
+    constexpr int SETS = sets_of(MODE, NMP);
+    constexpr long CHUNK_BYTES = (long)kColBlock * kChunkK * Tr::ELEM_BYTES;
+    typedef typename Tr::frag frag;
+    typedef WChunk<Tr, NMP, MODE> chunk_t;
+    extern __shared__ f32x4 lds[];
+
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    const int nw = blockDim.x >> 6;
+    const int r = lane & 15, q = lane >> 4;
+    const int jb = blockIdx.x;
+    const int tok0 = blockIdx.y * 16;
+    const int tc = min(p.T - tok0, 16);  // token lanes that carry data
+
+    const char *wbase = static_cast<const char *>(p.w) + (long)jb * p.NC * CHUNK_BYTES + lane * 16;
+    const char *w2base = static_cast<const char *>(p.w2) + (long)jb * p.NC * CHUNK_BYTES + lane * 16;
+    const uint32_t *mbase = p.m + ((long)jb * p.NC * kWave + lane) * NMP;
+
+    // LDS: [x fragments of this token block][hand-over area of the K-split reduction]
+    frag *lds_x = reinterpret_cast<frag *>(lds);
+    const int x_frags = p.NC * Tr::TILES * 4 * tc;
+    f32x4 *lds_red = lds + x_frags;
+
+    f32x4 acc[SETS][1];
+#pragma unroll
+    for (int s = 0; s < SETS; ++s) acc[s][0] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    auto load_chunk = [&](chunk_t &c, int kc) __attribute__((always_inline)) {
+        load_wchunk<Tr, NMP, MODE>(c, wbase + (long)kc * CHUNK_BYTES, w2base + (long)kc * CHUNK_BYTES,
+                                   mbase + (long)kc * kWave * NMP);
+    };
+    auto compute = [&](const chunk_t &c, int kc) __attribute__((always_inline)) {
+#pragma unroll
+        for (int t = 0; t < Tr::TILES; ++t) {
+            frag xf[1] = {frag{0, 0, 0, 0}};
+            if (r < tc) xf[0] = lds_x[((kc * Tr::TILES + t) * 4 + q) * tc + r];
+            mma_tile<Tr, NMP, 1, MODE>(acc, c, t, xf);
+        }
+    };
+
+    // ---- The ring of PF + 1 register buffers is indexed at compile time, so the steady-state loop is
+    //      unrolled by PF + 1; inside it every load is unconditional, which lets the compiler wait
+    //      for exactly the chunk it multiplies. ----
+    const int n_my = (p.NC - wave + nw - 1) / nw;  // chunks this wavefront owns (NC >= nw, so >= 1)
+    auto kc_of = [&](int i) __attribute__((always_inline)) { return wave + i * nw; };
+    chunk_t buf[PF + 1];
+    {
+        // Copy this token block's x into LDS in fragment order: fragment f = g * tc + row holds
+        // x[tok0 + row][g * LANE_K .. + LANE_K), zero beyond d_model.  The first group of x loads
+        // is issued before the first W loads and, hitting L2, returns before them.
+        constexpr int XG = 4;  // fragments per thread per group
+        const int nthr = blockDim.x;
+        auto x_load = [&](int f) __attribute__((always_inline)) {
+            const int fc = min(f, x_frags - 1);  // clamped: the load is always in bounds
+            const int row = fc % tc, g = fc / tc;
+            const long k0 = min((long)g * Tr::LANE_K, (long)p.h - Tr::LANE_K);
+            return *reinterpret_cast<const frag *>(static_cast<const char *>(p.x) +
+                                                   ((long)(tok0 + row) * p.h + k0) * Tr::ELEM_BYTES);
+        };
+        auto x_store = [&](int f, frag v) __attribute__((always_inline)) {
+            if (f < x_frags) {
+                if ((long)(f / tc) * Tr::LANE_K >= p.h) v = frag{0, 0, 0, 0};
+                lds_x[f] = v;
+            }
+        };
+        frag xv[XG];
+#pragma unroll
+        for (int b = 0; b < XG; ++b) xv[b] = x_load(threadIdx.x + b * nthr);
+#pragma unroll
+        for (int s = 0; s < PF; ++s) load_chunk(buf[s], kc_of(min(s, n_my - 1)));
+#pragma unroll
+        for (int b = 0; b < XG; ++b) x_store(threadIdx.x + b * nthr, xv[b]);
+        for (int f0 = threadIdx.x + XG * nthr; f0 < x_frags; f0 += XG * nthr) {
+#pragma unroll
+            for (int b = 0; b < XG; ++b) xv[b] = x_load(f0 + b * nthr);
+#pragma unroll
+            for (int b = 0; b < XG; ++b) x_store(f0 + b * nthr, xv[b]);
+        }
+        __syncthreads();
+    }
+
+    int i0 = 0;
+    for (; i0 + 2 * PF < n_my; i0 += PF + 1) {  // every stage of the group has a chunk left to load
+#pragma unroll
+        for (int s = 0; s <= PF; ++s) {
+            load_chunk(buf[(s + PF) % (PF + 1)], kc_of(i0 + s + PF));
+            compute(buf[s], kc_of(i0 + s));
+        }
+    }
+    // tail: at most 2 PF chunks; i0 is a multiple of PF + 1, so chunk i0 + s sits in buf[s % (PF + 1)]
+#pragma unroll
+    for (int s = 0; s < 2 * PF; ++s) {
+        const int i = i0 + s;
+        if (i >= n_my) break;  // uniform over the wavefront
+        if (i + PF < n_my) load_chunk(buf[(s + PF) % (PF + 1)], kc_of(i + PF));
+        compute(buf[s % (PF + 1)], kc_of(i));
+    }
+
+    // ---- combine the K split: wavefronts 1..nw-1 hand their sums to wavefront 0 through LDS,
+    //      which adds them in wavefront order (fixed order => reproducible bits) ----
+    if (nw > 1) {
+        if (wave > 0 && r < tc) {
+#pragma unroll
+            for (int s = 0; s < SETS; ++s) lds_red[((wave - 1) * SETS + s) * (4 * tc) + q * tc + r] = acc[s][0];
+        }
+        __syncthreads();
+        if (wave == 0 && r < tc) {
+            for (int w = 1; w < nw; ++w)
+#pragma unroll
+                for (int s = 0; s < SETS; ++s) acc[s][0] += lds_red[((w - 1) * SETS + s) * (4 * tc) + q * tc + r];
+        }
+    }
+    if (wave == 0) epilogue<Tr, NMP, 1, MODE>(p, acc, jb, tok0, r, q);
+}
+
+// ================================================================================================
+// Panel kernel: workgroup (jg, tg) owns NWC column blocks for the token group tg of 16 * TB tokens.
+// Wavefront (c, s) = (wave / NWK, wave % NWK) works on column block jg * NWC + c; its g-th chunk is
+// kc = g * NWK + s.  A panel is NWK * CPW consecutive chunks of K (CPW chunks per wavefront); the x
+// rows of a panel (all 16 * TB tokens) are staged once per workgroup into LDS in B-operand order,
+// double-buffered: the loads for panel i + 1 are issued before panel i is multiplied and written
+// to LDS after it, with one barrier per panel.
+// ================================================================================================
+template <typename Tr, int NMP, int TB, int MODE, int NWC, int NWK, int CPW>
+__global__ __launch_bounds__(NWC *NWK *kWave) MGLU_PANEL_OCCUPANCY(sets_of(MODE, NMP) * TB)
+void stream_panel_kernel(StreamParams p)
+{
+    constexpr int SETS = sets_of(MODE, NMP);
+    constexpr int NW = NWC * NWK;
+    constexpr long CHUNK_BYTES = (long)kColBlock * kChunkK * Tr::ELEM_BYTES;
+    constexpr int CHUNK_FRAG_TILES = Tr::TILES * TB;               // 1 KiB fragment tiles of x per chunk
+    constexpr int PANEL_FRAG_TILES = NWK * CPW * CHUNK_FRAG_TILES;
+    constexpr int XF = PANEL_FRAG_TILES / NW;                      // fragment tiles each wavefront stages
+    static_assert(PANEL_FRAG_TILES % NW == 0, "x panel must split evenly over the wavefronts");
+    typedef typename Tr::frag frag;
+    typedef WChunk<Tr, NMP, MODE> chunk_t;
+    extern __shared__ f32x4 lds[];
+    frag *lds_x = reinterpret_cast<frag *>(lds);                   // [2][PANEL_FRAG_TILES][64]
+
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    const int r = lane & 15, q = lane >> 4;
+    const int c = wave / NWK, s = wave % NWK;
+    const int jb = blockIdx.x * NWC + c;
+    const long jbc = min(jb, p.NB - 1);   // column blocks past the end: loads clamped, store dropped
+    const int tok0 = blockIdx.y * (16 * TB);
+
+    const char *wbase = static_cast<const char *>(p.w) + jbc * p.NC * CHUNK_BYTES + lane * 16;
+    const char *w2base = static_cast<const char *>(p.w2) + jbc * p.NC * CHUNK_BYTES + lane * 16;
+    const uint32_t *mbase = p.m + (jbc * p.NC * kWave + lane) * NMP;
+
+    f32x4 acc[SETS][TB];
+#pragma unroll
+    for (int st = 0; st < SETS; ++st)
+#pragma unroll
+        for (int tb = 0; tb < TB; ++tb) acc[st][tb] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    const int n_panels = (p.NC + NWK * CPW - 1) / (NWK * CPW);
+    auto load_chunk = [&](chunk_t &ck, int g) __attribute__((always_inline)) {
+        const long kc = min(g * NWK + s, p.NC - 1);   // clamped: always in bounds
+        load_wchunk<Tr, NMP, MODE>(ck, wbase + kc * CHUNK_BYTES, w2base + kc * CHUNK_BYTES, mbase + kc * kWave * NMP);
+    };
+    // fragment tile ft = (chunk-in-panel * TILES + t) * TB + tb; this wavefront stages ft = wave + NW i
+    auto x_load = [&](int panel, int i) __attribute__((always_inline)) {
+        const int ft = wave + NW * i;
+        const int ch = ft / CHUNK_FRAG_TILES, t = (ft / TB) % Tr::TILES, tb = ft % TB;
+        const long tok = min((long)tok0 + 16 * tb + r, (long)p.T - 1);
+        const long k0 = min((long)(panel * NWK * CPW + ch) * kChunkK + t * Tr::TILE_K + q * Tr::LANE_K,
+                            (long)p.h - Tr::LANE_K);
+        return *reinterpret_cast<const frag *>(static_cast<const char *>(p.x) + (tok * p.h + k0) * Tr::ELEM_BYTES);
+    };
+    auto x_store = [&](int buf, int panel, int i, frag v) __attribute__((always_inline)) {
+        const int ft = wave + NW * i;
+        const int ch = ft / CHUNK_FRAG_TILES, t = (ft / TB) % Tr::TILES, tb = ft % TB;
+        const bool ok = (tok0 + 16 * tb + r < p.T) &&
+                        ((long)(panel * NWK * CPW + ch) * kChunkK + t * Tr::TILE_K + q * Tr::LANE_K < p.h);
+        lds_x[(buf * PANEL_FRAG_TILES + ft) * kWave + lane] = ok ? v : frag{0, 0, 0, 0};
+    };
+    // multiply this wavefront's j-th chunk of a panel whose x sits in LDS buffer `buf`
+    auto compute = [&](const chunk_t &ck, int buf, int panel, int j) __attribute__((always_inline)) {
+        if ((panel * CPW + j) * NWK + s >= p.NC) return;   // no such chunk (tail of the last panel)
+        const frag *xb = lds_x + (buf * PANEL_FRAG_TILES + (j * NWK + s) * CHUNK_FRAG_TILES) * kWave + lane;
+#pragma unroll
+        for (int t = 0; t < Tr::TILES; ++t) {
+            frag xf[TB];
+#pragma unroll
+            for (int tb = 0; tb < TB; ++tb) xf[tb] = xb[(t * TB + tb) * kWave];
+            mma_tile<Tr, NMP, TB, MODE>(acc, ck, t, xf);
+        }
+    };
+
+    chunk_t bufs[2];
+    frag xv[XF];
+    // prologue: x of panel 0 first (L2 hits return ahead of the W loads issued after them)
+#pragma unroll
+    for (int i = 0; i < XF; ++i) xv[i] = x_load(0, i);
+    load_chunk(bufs[0], 0);
+#pragma unroll
+    for (int i = 0; i < XF; ++i) x_store(0, 0, i, xv[i]);
+    __syncthreads();
+
+    // One panel that has a successor: fetch the next panel's x, stream this panel's chunks (each
+    // multiply overlapped with the next chunk's loads), publish the next x.  PAR = register-buffer
+    // parity of the panel's first chunk and XB = its LDS buffer, both compile-time.
+    auto panel_step = [&](int panel, auto par_tag, auto xb_tag) __attribute__((always_inline)) {
+        constexpr int PAR = decltype(par_tag)::value, XB = decltype(xb_tag)::value;
+#pragma unroll
+        for (int i = 0; i < XF; ++i) xv[i] = x_load(panel + 1, i);
+#pragma unroll
+        for (int j = 0; j < CPW; ++j) {
+            load_chunk(bufs[(PAR + j + 1) & 1], panel * CPW + j + 1);
+            compute(bufs[(PAR + j) & 1], XB, panel, j);
+        }
+#pragma unroll
+        for (int i = 0; i < XF; ++i) x_store(XB ^ 1, panel + 1, i, xv[i]);
+        __syncthreads();
+    };
+    // The last panel: nothing left to stage, and no load after the final chunk.
+    auto last_panel = [&](int panel, auto par_tag, auto xb_tag) __attribute__((always_inline)) {
+        constexpr int PAR = decltype(par_tag)::value, XB = decltype(xb_tag)::value;
+#pragma unroll
+        for (int j = 0; j < CPW; ++j) {
+            if (j + 1 < CPW) load_chunk(bufs[(PAR + j + 1) & 1], panel * CPW + j + 1);
+            compute(bufs[(PAR + j) & 1], XB, panel, j);
+        }
+    };
+    typedef std::integral_constant<int, 0> I0;
+    typedef std::integral_constant<int, 1> I1;
+    constexpr int PAR1 = CPW & 1;   // parity of the first chunk of an odd panel
+    int pn = 0;
+    for (; pn + 2 < n_panels; pn += 2) {
+        panel_step(pn, I0{}, I0{});
+        panel_step(pn + 1, std::integral_constant<int, PAR1>{}, I1{});
+    }
+    if (n_panels - pn == 2) {
+        panel_step(pn, I0{}, I0{});
+        last_panel(pn + 1, std::integral_constant<int, PAR1>{}, I1{});
+    } else {
+        last_panel(pn, I0{}, I0{});
+    }
+
+    // ---- combine the K split per column block: wavefronts s > 0 hand their sums to (c, 0) through
+    //      LDS (the x buffers are free now), added in order of s ----
+    if constexpr (NWK > 1) {
+        __syncthreads();
+        if (s > 0) {
+#pragma unroll
+            for (int st = 0; st < SETS; ++st)
+#pragma unroll
+                for (int tb = 0; tb < TB; ++tb)
+                    lds[(((c * (NWK - 1) + s - 1) * SETS + st) * TB + tb) * kWave + lane] = acc[st][tb];
+        }
+        __syncthreads();
+        if (s == 0) {
+#pragma unroll
+            for (int w = 1; w < NWK; ++w)
+#pragma unroll
+                for (int st = 0; st < SETS; ++st)
+#pragma unroll
+                    for (int tb = 0; tb < TB; ++tb)
+                        acc[st][tb] += lds[(((c * (NWK - 1) + w - 1) * SETS + st) * TB + tb) * kWave + lane];
+        }
+    }
+    if (s == 0 && jb < p.NB) epilogue<Tr, NMP, TB, MODE>(p, acc, jb, tok0, r, q);
+}
+
 // ---- host side --------------------------------------------------------------------------------
 
-struct StreamLaunch {
-    int tb;         // token blocks (of 16) per workgroup
-    int nw;         // wavefronts per workgroup = K-split ways
-    bool xlds;      // x staged in LDS
-    size_t lds;     // dynamic LDS bytes
-    dim3 grid;
+// Largest token-block count per workgroup the 256-register budget allows in the panel kernel.
+int stream_max_token_blocks(int nmp, bool is_f32) { return is_f32 ? 1 : nmp <= 2 ? 4 : 2; }
+
+struct PanelWide  { static constexpr int NWC = 8, NWK = 1, CPW = 2; };
+struct PanelSplit { static constexpr int NWC = 4, NWK = 2, CPW = 1; };
+
+struct StreamPlan {
+    bool resident;
+    bool wide;     // panel kernel: PanelWide (else PanelSplit)
+    int tb;        // token blocks of 16 per workgroup
+    int nw;        // resident kernel: wavefronts per workgroup
+    size_t lds;
+    dim3 grid, block;
 };
 
-template <typename Tr, int NMP, int TB, int MODE, bool XLDS>
-static hipError_t launch_one(const StreamParams &p, const StreamLaunch &l, hipStream_t stream)
+static StreamPlan plan_stream(const StreamParams &p, bool is_f32, int nmp, int sets)
 {
-    constexpr int PF = XLDS ? MGLU_STREAM_PREFETCH_XLDS : 1;
-    auto kern = stream_kernel<Tr, NMP, TB, MODE, XLDS, PF>;
-    hipLaunchKernelGGL(kern, l.grid, dim3(l.nw * kWave), l.lds, stream, p);
+    constexpr size_t kLdsBudget = 56 * 1024;
+    const int elem = is_f32 ? 4 : 2;
+    const int tiles = is_f32 ? F32Traits::TILES : Bf16Traits::TILES;
+    StreamPlan pl = {};
+    // resident: one token block whose x rows (plus the reduction hand-over) fit the LDS budget
+    const int tc = p.T < 16 ? p.T : 16;
+    int nw = p.NC < MGLU_STREAM_MAX_WAVES ? p.NC : MGLU_STREAM_MAX_WAVES;
+    const size_t red = nw > 1 ? (size_t)(nw - 1) * sets * 4 * tc * sizeof(f32x4) : 0;
+    const size_t xb = (size_t)p.NC * kChunkK * tc * elem;
+    if (p.T <= 16 && xb + red <= kLdsBudget) {
+        pl.resident = true;
+        pl.tb = 1;
+        pl.nw = nw;
+        pl.lds = xb + red;
+        pl.grid = dim3(p.NB, 1);
+        pl.block = dim3(nw * kWave);
+        return pl;
+    }
+    const int blocks = (int)ceil_div(p.T, 16);
+    const int max_tb = stream_max_token_blocks(nmp, is_f32);
+    pl.resident = false;
+    pl.tb = (blocks >= 4 && max_tb >= 4) ? 4 : (blocks >= 2 && max_tb >= 2) ? 2 : 1;
+    pl.wide = ceil_div(p.NB, PanelWide::NWC) >= MGLU_PANEL_WIDE_MIN_WGS;
+    const int nwc = pl.wide ? PanelWide::NWC : PanelSplit::NWC;
+    const int nwk = pl.wide ? PanelWide::NWK : PanelSplit::NWK;
+    const int cpw = pl.wide ? PanelWide::CPW : PanelSplit::CPW;
+    const size_t xpanel = (size_t)2 * nwk * cpw * tiles * pl.tb * 1024;
+    const size_t redp = (size_t)nwc * (nwk - 1) * sets * pl.tb * 1024;
+    pl.lds = xpanel > redp ? xpanel : redp;
+    pl.grid = dim3((unsigned)ceil_div(p.NB, nwc), (unsigned)ceil_div(p.T, 16 * pl.tb));
+    pl.block = dim3(nwc * nwk * kWave);
+    return pl;
+}
+
+template <typename K>
+static hipError_t launch_kernel(K kern, const StreamParams &p, const StreamPlan &pl, hipStream_t stream)
+{
+    hipLaunchKernelGGL(kern, pl.grid, pl.block, pl.lds, stream, p);
     return hipGetLastError();
 }
 
-template <typename Tr, int NMP, int MODE>
-static hipError_t launch_tb(const StreamParams &p, const StreamLaunch &l, hipStream_t s)
+template <typename Tr, int NMP, int MODE, typename Shape>
+static hipError_t launch_panel(const StreamParams &p, const StreamPlan &pl, hipStream_t stream)
 {
-    // token blocks per workgroup are bounded by the 256-register budget: see stream_max_token_blocks
     constexpr bool kIsBf16 = Tr::ELEM_BYTES == 2;
-    if (l.tb == 1)
-        return l.xlds ? launch_one<Tr, NMP, 1, MODE, true>(p, l, s) : launch_one<Tr, NMP, 1, MODE, false>(p, l, s);
+    constexpr int NWC = Shape::NWC, NWK = Shape::NWK, CPW = Shape::CPW;
+    if (pl.tb == 1) return launch_kernel(stream_panel_kernel<Tr, NMP, 1, MODE, NWC, NWK, CPW>, p, pl, stream);
     if constexpr (kIsBf16) {
-        if (l.tb == 2) return launch_one<Tr, NMP, 2, MODE, false>(p, l, s);
+        if (pl.tb == 2) return launch_kernel(stream_panel_kernel<Tr, NMP, 2, MODE, NWC, NWK, CPW>, p, pl, stream);
         if constexpr (NMP <= 2) {
-            if (l.tb == 4) return launch_one<Tr, NMP, 4, MODE, false>(p, l, s);
+            if (pl.tb == 4) return launch_kernel(stream_panel_kernel<Tr, NMP, 4, MODE, NWC, NWK, CPW>, p, pl, stream);
         }
     }
     return hipErrorInvalidValue;
 }
 
-template <typename Tr, int MODE>
-static hipError_t launch_nmp(const StreamParams &p, int nmp, const StreamLaunch &l, hipStream_t s)
+template <typename Tr, int NMP, int MODE>
+static hipError_t launch_plan(const StreamParams &p, const StreamPlan &pl, hipStream_t stream)
 {
-    switch (nmp) {
-    case 1: return launch_tb<Tr, 1, MODE>(p, l, s);
-    case 2: return launch_tb<Tr, 2, MODE>(p, l, s);
-    case 4: return launch_tb<Tr, 4, MODE>(p, l, s);
-    default: return launch_tb<Tr, 8, MODE>(p, l, s);
-    }
+    if (pl.resident) return launch_kernel(stream_resident_kernel<Tr, NMP, MODE, MGLU_STREAM_PREFETCH>, p, pl, stream);
+    return pl.wide ? launch_panel<Tr, NMP, MODE, PanelWide>(p, pl, stream)
+                   : launch_panel<Tr, NMP, MODE, PanelSplit>(p, pl, stream);
 }
 
-// Largest token block count per workgroup the register budget allows for this mask count.
-int stream_max_token_blocks(int nmp, bool is_f32) { return is_f32 ? 1 : nmp <= 2 ? 4 : 2; }
+template <typename Tr, int MODE>
+static hipError_t launch_nmp(const StreamParams &p, int nmp, const StreamPlan &pl, hipStream_t s)
+{
+    switch (nmp) {
+    case 1: return launch_plan<Tr, 1, MODE>(p, pl, s);
+    case 2: return launch_plan<Tr, 2, MODE>(p, pl, s);
+    case 4: return launch_plan<Tr, 4, MODE>(p, pl, s);
+    default: return launch_plan<Tr, 8, MODE>(p, pl, s);
+    }
+}
 
 hipError_t launch_stream(const StreamParams &p, bool is_f32, int mode, hipStream_t stream)
 {
     const int nmp = (mode == kModeSwiglu) ? 1 : round_up_masks(p.n_masks);
-    const int sets = (mode == kModeSwiglu) ? 2 : 1 + nmp;
-    const int max_tb = stream_max_token_blocks(nmp, is_f32);
-    const int blocks = (int)ceil_div(p.T, 16);
-    const int elem = is_f32 ? 4 : 2;
-    constexpr size_t kLdsBudget = 64 * 1024;
-
-    StreamLaunch l;
-    l.tb = (blocks >= 4 && max_tb >= 4) ? 4 : (blocks >= 2 && max_tb >= 2) ? 2 : 1;
-    const int tc = (l.tb == 1) ? (p.T < 16 ? p.T : 16) : 16;
-
-    // wavefronts per workgroup: as many as there are chunks, at most MGLU_STREAM_MAX_WAVES,
-    // and the LDS hand-over area must fit
-    l.nw = p.NC < MGLU_STREAM_MAX_WAVES ? p.NC : MGLU_STREAM_MAX_WAVES;
-    auto red_bytes = [&](int n) { return n > 1 ? (size_t)(n - 1) * sets * l.tb * 4 * tc * sizeof(f32x4) : (size_t)0; };
-    while (l.nw > 1 && red_bytes(l.nw) > kLdsBudget) l.nw >>= 1;
-
-    const size_t x_bytes = (size_t)p.NC * kChunkK * tc * elem;
-    l.xlds = (l.tb == 1) && (x_bytes + red_bytes(l.nw) <= kLdsBudget);
-    l.lds = red_bytes(l.nw) + (l.xlds ? x_bytes : 0);
-    l.grid = dim3(p.NB, (unsigned)ceil_div(p.T, 16 * l.tb));
-
+    const StreamPlan pl = plan_stream(p, is_f32, nmp, sets_of(mode, nmp));
     if (is_f32) {
         switch (mode) {
-        case kModeMglu: return launch_nmp<F32Traits, kModeMglu>(p, nmp, l, stream);
-        case kModeProjections: return launch_nmp<F32Traits, kModeProjections>(p, nmp, l, stream);
-        default: return launch_tb<F32Traits, 1, kModeSwiglu>(p, l, stream);
+        case kModeMglu: return launch_nmp<F32Traits, kModeMglu>(p, nmp, pl, stream);
+        case kModeProjections: return launch_nmp<F32Traits, kModeProjections>(p, nmp, pl, stream);
+        default: return launch_plan<F32Traits, 1, kModeSwiglu>(p, pl, stream);
         }
     }
     switch (mode) {
-    case kModeMglu: return launch_nmp<Bf16Traits, kModeMglu>(p, nmp, l, stream);
-    case kModeProjections: return launch_nmp<Bf16Traits, kModeProjections>(p, nmp, l, stream);
-    default: return launch_tb<Bf16Traits, 1, kModeSwiglu>(p, l, stream);
+    case kModeMglu: return launch_nmp<Bf16Traits, kModeMglu>(p, nmp, pl, stream);
+    case kModeProjections: return launch_nmp<Bf16Traits, kModeProjections>(p, nmp, pl, stream);
+    default: return launch_plan<Bf16Traits, 1, kModeSwiglu>(p, pl, stream);
     }
 }
 
