@@ -55,6 +55,8 @@ mglu_status check_forward(const mglu_desc *d, bool need_masks)
                     d->d_model, lane_k);
     if ((long)d->tokens * d->d_ff > 0x7fffffff00L)
         return fail(MGLU_ERR_UNSUPPORTED, "tokens=%d x d_ff=%d is too large", d->tokens, d->d_ff);
+    if (d->tokens > 16 * 65535)   // token groups ride on gridDim.y
+        return fail(MGLU_ERR_UNSUPPORTED, "tokens=%d: at most %d tokens per call", d->tokens, 16 * 65535);
     return MGLU_OK;
 }
 

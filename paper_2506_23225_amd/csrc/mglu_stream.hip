@@ -183,7 +183,7 @@ __device__ __forceinline__ void epilogue(const StreamParams &p, const f32x4 (&ac
 // up to 16 tokens; its nw wavefronts take chunks kc = wave, wave + nw, ...
 // ================================================================================================
 template <typename Tr, int NMP, int MODE, int PF>
-__global__ __launch_bounds__(512) void stream_resident_kernel(StreamParams p)
+__global__ __launch_bounds__(MGLU_STREAM_MAX_WAVES *kWave) void stream_resident_kernel(StreamParams p)
 {
     constexpr int SETS = sets_of(MODE, NMP);
     constexpr long CHUNK_BYTES = (long)kColBlock * kChunkK * Tr::ELEM_BYTES;
@@ -504,9 +504,16 @@ static StreamPlan plan_stream(const StreamParams &p, bool is_f32, int nmp, int s
     return pl;
 }
 
+// gfx950 has 160 KiB of LDS per CU; a kernel may use more than the default 64 KiB of dynamic LDS
+// once it has been allowed to (asked once per kernel instantiation, not per launch).
+constexpr int kMaxDynamicLds = 160 * 1024;
+
 template <typename K>
 static hipError_t launch_kernel(K kern, const StreamParams &p, const StreamPlan &pl, hipStream_t stream)
 {
+    static hipError_t allowed = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                                    hipFuncAttributeMaxDynamicSharedMemorySize, kMaxDynamicLds);
+    if (pl.lds > 64 * 1024 && allowed != hipSuccess) return allowed;
     hipLaunchKernelGGL(kern, pl.grid, pl.block, pl.lds, stream, p);
     return hipGetLastError();
 }

@@ -55,6 +55,16 @@ def test_ragged_shapes(dtype, T, h, d, n_m):
     _check_full(x, W, masks, _run(x, W, masks))
 
 
+@pytest.mark.parametrize("T,h,d,n_m", [(40, 384, 25616, 2), (17, 136, 25608, 8), (64, 640, 25600, 1)])
+def test_wide_panel_shape_ragged(T, h, d, n_m):
+    """d_ff large enough for the 8-column-block workgroup shape of the panel kernel, with a ragged
+    column tail, an odd number of K chunks and token counts that leave partial token blocks."""
+    x, W, masks = synth.make_inputs(h, d, n_m, T, dtype="bf16", seed=T + h + d, device=DEV)
+    out = _run(x, W, masks)
+    cols = edge_columns(d, n_random=256, seed=T)
+    _check_columns(x, W, masks, out, cols)
+
+
 @pytest.mark.parametrize("T,h,d,n_m", [
     (65, 128, 16, 1), (128, 256, 128, 4), (200, 520, 272, 4), (300, 384, 1000, 8), (129, 1024, 130, 2),
     (257, 136, 2064, 1), (1100, 256, 300, 3), (96, 2048, 144, 8),
