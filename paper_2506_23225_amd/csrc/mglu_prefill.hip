@@ -36,11 +36,20 @@
 
 namespace mglu {
 
-constexpr int kPrefillWaves = 8;
+// In which tile of a chunk the s-th x piece of the next chunk is loaded / written to LDS.
+#ifndef MGLU_PREFILL_XLOAD_TILE
+#define MGLU_PREFILL_XLOAD_TILE(s, n) ((s) * 3 / (n))
+#define MGLU_PREFILL_XSTORE_TILE(s, n) ((s) * 3 / (n) + 1)
+#endif
+#ifndef MGLU_PREFILL_WAVES
+#define MGLU_PREFILL_WAVES 8   // wavefronts per workgroup (8: one workgroup per CU; 4: two)
+#endif
+constexpr int kPrefillWaves = MGLU_PREFILL_WAVES;
 
 // AD: how many tiles ahead of the multiply the A fragments are fetched.
 template <int NMP, int CB, int TB, int MODE, int AD>
-__global__ __launch_bounds__(kPrefillWaves *kWave) void prefill_kernel(PrefillParams p)
+__global__ __launch_bounds__(kPrefillWaves *kWave) __attribute__((amdgpu_waves_per_eu(2, 2)))
+void prefill_kernel(PrefillParams p)
 {
     typedef Bf16Traits Tr;
     typedef Tr::frag frag;
@@ -53,8 +62,11 @@ __global__ __launch_bounds__(kPrefillWaves *kWave) void prefill_kernel(PrefillPa
     frag *lds_x = reinterpret_cast<frag *>(lds_raw);   // [2][tile t<4][tb<TB][lane<64]
 
     const int lane = threadIdx.x & 63;
-    const int wave = threadIdx.x >> 6;
+    // the wavefront index is uniform over the wavefront: say so, and every address below splits into
+    // a scalar base plus a 32-bit per-lane offset (no 64-bit vector arithmetic per load)
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int r = lane & 15, q = lane >> 4;
+    const uint32_t lane16 = lane * 16;
 
     // ---- XCD-aware tile order: ids equal mod 8 share an L2; give each XCD a band of column
     //      tiles and walk it in patches of p.group_m token tiles ----
@@ -76,16 +88,17 @@ __global__ __launch_bounds__(kPrefillWaves *kWave) void prefill_kernel(PrefillPa
     const int jb0 = (tile_n * kPrefillWaves + wave) * CB;   // first column block of this wavefront
 
     // column blocks past the end are clamped for the loads and dropped at the store
-    const char *wbase[CB];
+    const char *wbase[CB];       // scalar: start of the column block's weight stream
     const char *w2base[CB];
-    const uint32_t *mbase[CB];
+    const char *mbase[CB];       // scalar: start of its mask words
 #pragma unroll
     for (int cb = 0; cb < CB; ++cb) {
         const long jb = min(jb0 + cb, p.NB - 1);
-        wbase[cb] = static_cast<const char *>(p.w) + jb * p.NC * CHUNK_BYTES + lane * 16;
-        w2base[cb] = static_cast<const char *>(p.w2) + jb * p.NC * CHUNK_BYTES + lane * 16;
-        mbase[cb] = p.m + (jb * p.NC * kWave + lane) * NMP;
+        wbase[cb] = static_cast<const char *>(p.w) + jb * p.NC * CHUNK_BYTES;
+        w2base[cb] = static_cast<const char *>(p.w2) + jb * p.NC * CHUNK_BYTES;
+        mbase[cb] = reinterpret_cast<const char *>(p.m) + jb * p.NC * (kWave * NMP * 4);
     }
+    const uint32_t lane_m = lane * (NMP * 4);
 
     f32x4 acc[SETS][CB][TB];
 #pragma unroll
@@ -95,25 +108,28 @@ __global__ __launch_bounds__(kPrefillWaves *kWave) void prefill_kernel(PrefillPa
 #pragma unroll
             for (int tb = 0; tb < TB; ++tb) acc[s][cb][tb] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    // ---- x staging: wavefront w copies fragments idx = w + 8 s (idx = tb * 4 + t) of a chunk:
+    // ---- x staging: wavefront w copies fragments idx = w + NW s (idx = tb * 4 + t) of a chunk:
     //      lane (r, q) moves x[tok0 + 16 tb + r][128 kc + 32 t + 8 q .. + 8) to LDS slot
-    //      (t * TB + tb) * 64 + lane, the order the B operand is read in ----
-    auto x_src = [&](int kc, int s) {
-        const int idx = wave + kPrefillWaves * s;
-        const int tb = idx >> 2, t = idx & 3;
-        const long tok = min((long)tok0 + 16 * tb + r, (long)p.T - 1);
-        const long k0 = min((long)kc * kChunkK + 32 * t + 8 * q, (long)p.h - 8);
-        return reinterpret_cast<const frag *>(static_cast<const char *>(p.x) + (tok * p.h + k0) * 2);
+    //      (t * TB + tb) * 64 + lane, the order the B operand is read in.  Token rows past T are
+    //      clamped to the last row (their outputs are never stored) and k past d_model to the
+    //      row's last fragment (W is zero-padded there, so whatever finite x is read adds 0). ----
+    const char *xbase = static_cast<const char *>(p.x) + (long)tok0 * p.h * 2;   // scalar
+    const uint32_t klim = (uint32_t)(p.h - 8) * 2;
+    uint32_t xrow[XPIECES];      // per piece: byte offset of this lane's token row from xbase
+#pragma unroll
+    for (int s = 0; s < XPIECES; ++s) {
+        const int tb = (wave + kPrefillWaves * s) >> 2;
+        xrow[s] = (uint32_t)(min(tok0 + 16 * tb + r, p.T - 1) - tok0) * (uint32_t)(p.h * 2);
+    }
+    auto x_src = [&](int kc, int s) __attribute__((always_inline)) {
+        const int t = (wave + kPrefillWaves * s) & 3;
+        const uint32_t kb = min((uint32_t)(kc * kChunkK + 32 * t) * 2 + q * 16, klim);
+        return reinterpret_cast<const frag *>(xbase + (xrow[s] + kb));
     };
-    auto x_dst = [&](int buf, int s) {
+    auto x_dst = [&](int buf, int s) __attribute__((always_inline)) {
         const int idx = wave + kPrefillWaves * s;
         const int tb = idx >> 2, t = idx & 3;
         return lds_x + ((buf * 4 + t) * TB + tb) * kWave + lane;
-    };
-    auto x_valid = [&](int kc, int s) {
-        const int idx = wave + kPrefillWaves * s;
-        const int t = idx & 3;
-        return kc * kChunkK + 32 * t + 8 * q < p.h;   // beyond d_model: zero (W is zero-padded there too)
     };
 
     // ---- A ring: entry t holds the fragments of tile t of the current (or next) chunk ----
@@ -121,19 +137,21 @@ __global__ __launch_bounds__(kPrefillWaves *kWave) void prefill_kernel(PrefillPa
     frag aw2[MODE == kModeSwiglu ? AR : 1][CB];
     uint32_t mk[2][CB][NMP];   // mask words of the current and the next chunk
 
-    auto load_a = [&](int kc, int t, int slot) {
+    auto load_a = [&](int kc, int t, int slot) __attribute__((always_inline)) {
 #pragma unroll
         for (int cb = 0; cb < CB; ++cb) {
-            aw[slot][cb] = *reinterpret_cast<const frag *>(wbase[cb] + (long)kc * CHUNK_BYTES + t * 1024);
+            aw[slot][cb] = *reinterpret_cast<const frag *>(wbase[cb] + (long)kc * CHUNK_BYTES + t * 1024 + lane16);
             if constexpr (MODE == kModeSwiglu)
-                aw2[slot][cb] = *reinterpret_cast<const frag *>(w2base[cb] + (long)kc * CHUNK_BYTES + t * 1024);
+                aw2[slot][cb] =
+                    *reinterpret_cast<const frag *>(w2base[cb] + (long)kc * CHUNK_BYTES + t * 1024 + lane16);
         }
     };
-    auto load_masks = [&](int kc, int slot) {
+    auto load_masks = [&](int kc, int slot) __attribute__((always_inline)) {
         if constexpr (MODE != kModeSwiglu) {
 #pragma unroll
             for (int cb = 0; cb < CB; ++cb) {
-                const uint32_t *mp = mbase[cb] + (long)kc * kWave * NMP;
+                const uint32_t *mp =
+                    reinterpret_cast<const uint32_t *>(mbase[cb] + (long)kc * (kWave * NMP * 4) + lane_m);
                 if constexpr (NMP == 8) {
                     u32x4 a = *reinterpret_cast<const u32x4 *>(mp), b = *(reinterpret_cast<const u32x4 *>(mp) + 1);
 #pragma unroll
@@ -162,12 +180,12 @@ __global__ __launch_bounds__(kPrefillWaves *kWave) void prefill_kernel(PrefillPa
 #pragma unroll
         for (int t = 0; t < AD; ++t) load_a(0, t, t);
 #pragma unroll
-        for (int s = 0; s < XPIECES; ++s) *x_dst(0, s) = x_valid(0, s) ? xv[s] : frag{0, 0, 0, 0};
+        for (int s = 0; s < XPIECES; ++s) *x_dst(0, s) = xv[s];
     }
     __syncthreads();
 
     // One chunk of the K loop; MS = which half of mk[] holds this chunk's masks (compile time).
-    auto chunk_step = [&](int kc, auto ms_tag) {
+    auto chunk_step = [&](int kc, auto ms_tag) __attribute__((always_inline)) {
         constexpr int MS = decltype(ms_tag)::value;
         const int buf = kc & 1;
         const int kn = min(kc + 1, last);   // next chunk, clamped: its loads are then always in bounds
@@ -180,7 +198,7 @@ __global__ __launch_bounds__(kPrefillWaves *kWave) void prefill_kernel(PrefillPa
             // first use, which would expose the whole memory latency.
 #pragma unroll
             for (int s = 0; s < XPIECES; ++s)
-                if (s * 3 / XPIECES == t) xv[s] = *x_src(kn, s);
+                if (MGLU_PREFILL_XLOAD_TILE(s, XPIECES) == t) xv[s] = *x_src(kn, s);
             if (t + AD < 4) load_a(kc, t + AD, (t + AD) % AR);
             else load_a(kn, t + AD - 4, (t + AD) % AR);
             if (t == 0) load_masks(kn, MS ^ 1);
@@ -209,7 +227,7 @@ __global__ __launch_bounds__(kPrefillWaves *kWave) void prefill_kernel(PrefillPa
             }
 #pragma unroll
             for (int s = 0; s < XPIECES; ++s)   // a piece is stored one tile after its load was issued
-                if (s * 3 / XPIECES + 1 == t) *x_dst(buf ^ 1, s) = x_valid(kn, s) ? xv[s] : frag{0, 0, 0, 0};
+                if (MGLU_PREFILL_XSTORE_TILE(s, XPIECES) == t) *x_dst(buf ^ 1, s) = xv[s];
         }
         __syncthreads();
     };
