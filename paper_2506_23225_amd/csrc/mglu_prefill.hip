@@ -60,6 +60,8 @@ void prefill_kernel(PrefillParams p)
     static_assert(TB * 4 % kPrefillWaves == 0, "token blocks must split evenly over the wavefronts");
     extern __shared__ f32x4 lds_raw[];
     frag *lds_x = reinterpret_cast<frag *>(lds_raw);   // [2][tile t<4][tb<TB][lane<64]
+    // byte address of that array inside LDS, for the hand-placed reads
+    const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char *)lds_raw;
 
     const int lane = threadIdx.x & 63;
     // the wavefront index is uniform over the wavefront: say so, and every address below splits into
@@ -190,6 +192,22 @@ void prefill_kernel(PrefillParams p)
         const int buf = kc & 1;
         const int kn = min(kc + 1, last);   // next chunk, clamped: its loads are then always in bounds
         frag xv[XPIECES];
+        // B fragments are read from LDS one pair of token blocks ahead of the MFMAs that use them
+        // (the compiler, left alone, issues each read right before its use and eats the LDS latency
+        // three times per tile).  The first pair of a chunk cannot be fetched before the barrier.
+        constexpr int PAIRS = TB / 2;
+        static_assert(TB % 2 == 0, "token blocks are processed in pairs");
+        // The reads are written as assembly so that they stay where they are put; the matching
+        // waits name the registers they release, which orders every use after them.  (lgkmcnt
+        // counts LDS operations in order, so "at most 2 newer ones outstanding" means the pair
+        // before them has landed; anything else in flight only makes the wait stricter.)
+        const uint32_t xchunk = lds_base + (uint32_t)(buf * 4 * TB * kWave + lane) * 16u;
+        auto read_pair = [&](frag (&b)[2], int t, int pi) __attribute__((always_inline)) {
+            asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(b[0]) : "v"(xchunk), "n"((t * TB + 2 * pi) * 1024));
+            asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(b[1]) : "v"(xchunk), "n"((t * TB + 2 * pi + 1) * 1024));
+        };
+        frag bcur[2], bnxt[2];
+        read_pair(bcur, 0, 0);
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
             // Issue this tile's prefetches first: pieces of the next chunk's x (stored one tile
@@ -216,14 +234,23 @@ void prefill_kernel(PrefillParams p)
                     for (int i = 0; i < NMP; ++i) var[1 + i][cb] = Tr::template flip<NMP>(aw[t][cb], mk[MS][cb], t, i);
                 }
             }
-            const frag *xb = lds_x + ((buf * 4 + t) * TB) * kWave + lane;
 #pragma unroll
-            for (int tb = 0; tb < TB; ++tb) {
-                const frag b = xb[tb * kWave];
+            for (int pi = 0; pi < PAIRS; ++pi) {
+                const bool more = (pi + 1 < PAIRS) || (t + 1 < 4);
+                if (more) {
+                    read_pair(bnxt, pi + 1 < PAIRS ? t : t + 1, pi + 1 < PAIRS ? pi + 1 : 0);
+                    asm volatile("s_waitcnt lgkmcnt(2)" : "+v"(bcur[0]), "+v"(bcur[1]));
+                } else {
+                    asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(bcur[0]), "+v"(bcur[1]));
+                }
 #pragma unroll
-                for (int s = 0; s < SETS; ++s)
+                for (int h2 = 0; h2 < 2; ++h2)
 #pragma unroll
-                    for (int cb = 0; cb < CB; ++cb) acc[s][cb][tb] = Tr::mma(var[s][cb], b, acc[s][cb][tb]);
+                    for (int s = 0; s < SETS; ++s)
+#pragma unroll
+                        for (int cb = 0; cb < CB; ++cb)
+                            acc[s][cb][2 * pi + h2] = Tr::mma(var[s][cb], bcur[h2], acc[s][cb][2 * pi + h2]);
+                if (more) { bcur[0] = bnxt[0]; bcur[1] = bnxt[1]; }
             }
 #pragma unroll
             for (int s = 0; s < XPIECES; ++s)   // a piece is stored one tile after its load was issued
