@@ -75,6 +75,28 @@ def test_prefill_kernel_ragged_shapes(T, h, d, n_m):
     _check_full(x, W, masks, _run(x, W, masks))
 
 
+def test_kernel_hand_over_at_64_tokens():
+    """64 tokens run on the streaming (panel) kernel, 65 on the MFMA-tiled one: both against the oracle,
+    and the shared rows against each other (they may differ by summation order only)."""
+    x, W, masks = synth.make_inputs(768, 272, 6, 65, dtype="bf16", seed=64, device=DEV)
+    out65 = _run(x, W, masks)
+    out64 = _run(x[:64].contiguous(), W, masks)
+    _check_full(x, W, masks, out65)
+    _check_full(x[:64], W, masks, out64)
+    assert rel_err(to_np64(out64), to_np64(out65[:64])) <= 1e-2
+
+
+def test_prefill_kernel_other_layout_and_entries():
+    """The tiled kernel through the NK layout, the unpacked-input entry and non-0/1 mask bytes."""
+    x, W, masks = synth.make_inputs(520, 200, 7, 130, dtype="bf16", seed=9, device=DEV)
+    ref = _run(x, W, masks)
+    _check_full(x, W, masks, ref)
+    Wt, Mt = W.t().contiguous(), masks.transpose(1, 2).contiguous()
+    assert torch.equal(_run(x, Wt, Mt, layout="nk"), ref)
+    assert torch.equal(_run(x, W, masks, via_bool=True), ref)
+    assert torch.equal(_run(x, W, masks * 255), ref)           # any non-zero byte means "gate"
+
+
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
 def test_nk_layout_and_bool_entry(dtype):
     x, W, masks = synth.make_inputs(392, 72, 3, 4, dtype=dtype, seed=5, device=DEV)
