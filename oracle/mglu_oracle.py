@@ -24,6 +24,13 @@ def _load():
         lib.mglu_oracle_forward.restype = ctypes.c_int
         lib.swiglu_oracle_forward.argtypes = [dp, dp, dp] + [ctypes.c_long] * 3 + [dp]
         lib.swiglu_oracle_forward.restype = ctypes.c_int
+        lib.mglu_oracle_forward_variant.argtypes = ([dp, dp, bp] + [ctypes.c_long] * 4
+                                                    + [ctypes.c_int, ctypes.c_int, dp, dp])
+        lib.mglu_oracle_forward_variant.restype = ctypes.c_int
+        lib.mglu_oracle_route_topk.argtypes = [dp, dp] + [ctypes.c_long] * 4 + [dp]
+        lib.mglu_oracle_route_topk.restype = ctypes.c_int
+        lib.linear_oracle_forward.argtypes = [dp, dp] + [ctypes.c_long] * 3 + [dp]
+        lib.linear_oracle_forward.restype = ctypes.c_int
         lib.mglu_oracle_threads.restype = ctypes.c_int
         _lib = lib
     return _lib
@@ -89,4 +96,68 @@ def swiglu_forward(x, Wg, Wv):
     rc = _load().swiglu_oracle_forward(_dptr(x), _dptr(Wg), _dptr(Wv), T, h, d, _dptr(out))
     if rc != 0:
         raise RuntimeError("swiglu_oracle_forward failed with code %d" % rc)
+    return out
+
+
+GATE_FN = {"swish": 0, "gelu": 1, "relu": 2}
+MASK_USE = {"both": 0, "dense_gate": 1, "dense_value": 2, "none": 3}
+
+
+def _masks_u8(masks):
+    M = np.ascontiguousarray(np.asarray(masks))
+    if M.dtype == np.bool_:
+        M = M.view(np.uint8)
+    if M.dtype != np.uint8:
+        raise TypeError("masks must be bool or uint8")
+    return M
+
+
+def mglu_forward_variant(x, W, masks, gate="swish", mask_use="both", route=None):
+    """Eq. 3 with the appendix's variations: another gate function, the partial-mask ablations,
+    per-token route weights (Top-K routing).  route: None or [T, n_m]."""
+    x, W, M = _f64(x), _f64(W), _masks_u8(masks)
+    T, h = x.shape
+    d = W.shape[1]
+    n_m = M.shape[0]
+    if W.shape[0] != h or M.shape[1:] != (h, d):
+        raise ValueError("shape mismatch")
+    r = None
+    if route is not None:
+        r = _f64(route)
+        if r.shape != (T, n_m):
+            raise ValueError("route must be [T, n_m]")
+    out = np.empty((T, d), dtype=np.float64)
+    rc = _load().mglu_oracle_forward_variant(
+        _dptr(x), _dptr(W), M.ctypes.data_as(ctypes.POINTER(ctypes.c_uint8)), T, h, d, n_m,
+        GATE_FN[gate], MASK_USE[mask_use], _dptr(r) if r is not None else ctypes.POINTER(ctypes.c_double)(),
+        _dptr(out))
+    if rc != 0:
+        raise RuntimeError("mglu_oracle_forward_variant failed with code %d" % rc)
+    return out
+
+
+def route_topk(x, Wr, k):
+    """Top-K router weights [T, n_m]: softmax over the k largest logits of x Wr, 0 elsewhere."""
+    x, Wr = _f64(x), _f64(Wr)
+    T, h = x.shape
+    n_m = Wr.shape[1]
+    if Wr.shape[0] != h:
+        raise ValueError("shape mismatch")
+    w = np.empty((T, n_m), dtype=np.float64)
+    rc = _load().mglu_oracle_route_topk(_dptr(x), _dptr(Wr), T, h, n_m, int(k), _dptr(w))
+    if rc != 0:
+        raise RuntimeError("mglu_oracle_route_topk failed with code %d" % rc)
+    return w
+
+
+def linear_forward(a, W):
+    """out = a W: a [T,K], W [K,N]."""
+    a, W = _f64(a), _f64(W)
+    T, K = a.shape
+    if W.shape[0] != K:
+        raise ValueError("shape mismatch")
+    out = np.empty((T, W.shape[1]), dtype=np.float64)
+    rc = _load().linear_oracle_forward(_dptr(a), _dptr(W), T, K, W.shape[1], _dptr(out))
+    if rc != 0:
+        raise RuntimeError("linear_oracle_forward failed with code %d" % rc)
     return out
