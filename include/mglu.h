@@ -132,6 +132,63 @@ mglu_status mglu_projections(const mglu_desc *desc, const void *x_dev, const voi
                              float *value_dev, void *workspace_dev, size_t workspace_bytes,
                              void *stream);
 
+/* ---- variants from the paper's appendix, and the projection that follows the layer -------- */
+
+/* Gate function g of Eq. 3 (appendix "Other Activation Functions": SwiMGLU, GeMGLU, ReMGLU). */
+typedef enum {
+    MGLU_GATE_SWISH = 0,   /* z * sigmoid(z), the main paper's choice */
+    MGLU_GATE_GELU = 1,    /* z * Phi(z), exact Gaussian CDF */
+    MGLU_GATE_RELU = 2     /* max(z, 0) */
+} mglu_gate_fn;
+
+/* Which branches see the masks (appendix "Partial Mask Ablation"); summed over masks as in Eq. 3. */
+typedef enum {
+    MGLU_MASK_BOTH = 0,        /* g(x (M_i*W))  * x ((1-M_i)*W)   Eq. 3 */
+    MGLU_MASK_VALUE_ONLY = 1,  /* g(x W)        * x ((1-M_i)*W)   "No Gate Mask" (dense gate) */
+    MGLU_MASK_GATE_ONLY = 2,   /* g(x (M_i*W))  * x W             "No Value Mask" (dense value) */
+    MGLU_MASK_NONE = 3         /* g(x W)        * x W             "No Masks" */
+} mglu_mask_use;
+
+typedef struct {
+    mglu_gate_fn gate;
+    mglu_mask_use mask_use;
+    /* Per-token route weights G(x)_i of the Top-K routed layer (appendix "Top-K Routing"):
+     *   out = sum_i G(x)_i g(x (M_i*W)) * x ((1-M_i)*W).
+     * dev, fp32 [tokens][n_masks], e.g. from mglu_route_topk; NULL means every weight is 1.
+     * In the decode path (tokens <= 16, x resident in LDS) a mask whose weight is 0 for every
+     * token of the call is skipped entirely -- no operand preparation, no MFMA. */
+    const float *route_weights_dev;
+} mglu_variant;
+
+/* mglu_forward with the variations above; a NULL variant, or {SWISH, BOTH, NULL}, is mglu_forward. */
+mglu_status mglu_forward_variant(const mglu_desc *desc, const mglu_variant *variant, const void *x_dev,
+                                 const void *W_packed_dev, const void *masks_packed_dev, void *out_dev,
+                                 void *workspace_dev, size_t workspace_bytes, void *stream);
+
+/* Router of the Top-K routed layer: logits = x Wr, the k largest per token are kept (on equal
+ * logits the lower mask index wins), softmax over the kept ones, 0 elsewhere.
+ *   x_dev [tokens][d_model] and Wr_dev [d_model][n_masks] in desc->dtype; 1 <= k <= n_masks;
+ *   weights_dev fp32 [tokens][n_masks], fully overwritten.  desc->d_ff is ignored. */
+mglu_status mglu_route_topk(const mglu_desc *desc, const void *x_dev, const void *Wr_dev, int k,
+                            float *weights_dev, void *stream);
+
+/* Plain projection out = a W with the same packed weight format and kernels (no masks, no
+ * activation): the output projection W_o in R^{d x h} that maps the layer's result back to the
+ * hidden size (Method, after Eq. 1).  Here desc->d_model is the REDUCTION length (rows of the
+ * unpacked W, = d_ff of the layer for W_o) and desc->d_ff the OUTPUT width (= d_model of the layer);
+ * desc->n_masks is ignored.  a_dev [tokens][reduction], out_dev [tokens][output], desc->dtype. */
+mglu_status mglu_linear_forward(const mglu_desc *desc, const void *a_dev, const void *W_packed_dev,
+                                void *out_dev, void *workspace_dev, size_t workspace_bytes, void *stream);
+
+/* The whole gated FFN block: y = MGLU(x) Wo, as two launches on `stream`.  desc describes the MGLU
+ * layer; Wo_packed_dev comes from mglu_pack_weights with d_model and d_ff exchanged (Wo is
+ * [d_ff][d_model] in the KN layout); hidden_dev [tokens][d_ff] is caller-owned scratch for the
+ * intermediate representation; y_dev [tokens][d_model].  variant may be NULL. */
+mglu_status mglu_ffn_forward(const mglu_desc *desc, const mglu_variant *variant, const void *x_dev,
+                             const void *W_packed_dev, const void *masks_packed_dev,
+                             const void *Wo_packed_dev, void *hidden_dev, void *y_dev,
+                             void *workspace_dev, size_t workspace_bytes, void *stream);
+
 /* ---- reference points for measurement ---------------------------------------------------- */
 
 /* Two-matrix SwiGLU projection of the same shape (Eq. 1 with g = Swish), the paper's

@@ -19,6 +19,13 @@ class MgluDesc(ctypes.Structure):
                 ("n_masks", ctypes.c_int32), ("dtype", ctypes.c_int), ("w_layout", ctypes.c_int)]
 
 
+class MgluVariant(ctypes.Structure):
+    _fields_ = [("gate", ctypes.c_int), ("mask_use", ctypes.c_int), ("route_weights_dev", ctypes.c_void_p)]
+
+
+MGLU_GATE = {"swish": 0, "gelu": 1, "relu": 2}
+MGLU_MASK_USE = {"both": 0, "dense_gate": 1, "dense_value": 2, "none": 3}
+
 # every symbol include/mglu.h declares: name -> (restype, argtypes)
 _P = ctypes.c_void_p
 _D = ctypes.POINTER(MgluDesc)
@@ -34,6 +41,10 @@ SIGNATURES = {
     "mglu_forward_bool_workspace_bytes": (_SZ, [_D]),
     "mglu_forward_bool": (ctypes.c_int, [_D, _P, _P, _P, _P, _P, _SZ, _P]),
     "mglu_projections": (ctypes.c_int, [_D, _P, _P, _P, _P, _P, _P, _P, _SZ, _P]),
+    "mglu_forward_variant": (ctypes.c_int, [_D, ctypes.POINTER(MgluVariant), _P, _P, _P, _P, _P, _SZ, _P]),
+    "mglu_route_topk": (ctypes.c_int, [_D, _P, _P, ctypes.c_int, _P, _P]),
+    "mglu_linear_forward": (ctypes.c_int, [_D, _P, _P, _P, _P, _SZ, _P]),
+    "mglu_ffn_forward": (ctypes.c_int, [_D, ctypes.POINTER(MgluVariant), _P, _P, _P, _P, _P, _P, _P, _SZ, _P]),
     "swiglu_forward": (ctypes.c_int, [_D, _P, _P, _P, _P, _P, _SZ, _P]),
     "mglu_stream_read": (ctypes.c_int, [_P, _SZ, _P, _P]),
     "mglu_last_error": (ctypes.c_char_p, []),

@@ -4,6 +4,8 @@ torch is used for device memory and the current HIP stream; every step of the
 MGLU path runs in the library's kernels.  Tensors must live on the GPU and be
 contiguous.
 """
+import ctypes
+
 import torch
 
 from . import _lib
@@ -96,6 +98,63 @@ def mglu_forward(desc, x, W_packed, masks_packed, out=None, workspace=None):
                                     _ptr(masks_packed, "masks_packed"), _ptr(out, "out"),
                                     _ptr(workspace, "workspace"), ws_bytes, _stream(x)))
     return out
+
+
+def _variant(gate, mask_use, route_weights):
+    if gate == "swish" and mask_use == "both" and route_weights is None:
+        return None, None
+    if route_weights is not None and route_weights.dtype != torch.float32:
+        raise ValueError("route_weights must be float32")
+    v = _lib.MgluVariant(_lib.MGLU_GATE[gate], _lib.MGLU_MASK_USE[mask_use], _ptr(route_weights, "route_weights"))
+    return v, ctypes.byref(v)
+
+
+def mglu_forward_variant(desc, x, W_packed, masks_packed, gate="swish", mask_use="both", route_weights=None,
+                         out=None, workspace=None):
+    """mglu_forward with another gate function, a partial-mask ablation and/or per-token route weights."""
+    if out is None:
+        out = torch.empty(desc.tokens, desc.d_ff, dtype=x.dtype, device=x.device)
+    workspace, ws_bytes = _workspace(desc, x.device, workspace)
+    keep, ref = _variant(gate, mask_use, route_weights)
+    _check(_lib.load().mglu_forward_variant(desc, ref, _ptr(x, "x"), _ptr(W_packed, "W_packed"),
+                                            _ptr(masks_packed, "masks_packed"), _ptr(out, "out"),
+                                            _ptr(workspace, "workspace"), ws_bytes, _stream(x)))
+    return out
+
+
+def mglu_route_topk(desc, x, Wr, k, weights=None):
+    """Top-K router: softmax over the k largest logits of x Wr per token, 0 elsewhere; fp32 [T, n_masks]."""
+    if weights is None:
+        weights = torch.empty(desc.tokens, desc.n_masks, dtype=torch.float32, device=x.device)
+    _check(_lib.load().mglu_route_topk(desc, _ptr(x, "x"), _ptr(Wr, "Wr"), int(k), _ptr(weights, "weights"),
+                                       _stream(x)))
+    return weights
+
+
+def mglu_linear_forward(desc, a, W_packed, out=None, workspace=None):
+    """out = a W; desc.d_model is the reduction length, desc.d_ff the output width."""
+    if out is None:
+        out = torch.empty(desc.tokens, desc.d_ff, dtype=a.dtype, device=a.device)
+    workspace, ws_bytes = _workspace(desc, a.device, workspace)
+    _check(_lib.load().mglu_linear_forward(desc, _ptr(a, "a"), _ptr(W_packed, "W_packed"), _ptr(out, "out"),
+                                           _ptr(workspace, "workspace"), ws_bytes, _stream(a)))
+    return out
+
+
+def mglu_ffn_forward(desc, x, W_packed, masks_packed, Wo_packed, gate="swish", mask_use="both",
+                     route_weights=None, hidden=None, y=None, workspace=None):
+    """y = MGLU(x) Wo (two launches); returns (y, hidden)."""
+    if hidden is None:
+        hidden = torch.empty(desc.tokens, desc.d_ff, dtype=x.dtype, device=x.device)
+    if y is None:
+        y = torch.empty(desc.tokens, desc.d_model, dtype=x.dtype, device=x.device)
+    workspace, ws_bytes = _workspace(desc, x.device, workspace)
+    keep, ref = _variant(gate, mask_use, route_weights)
+    _check(_lib.load().mglu_ffn_forward(desc, ref, _ptr(x, "x"), _ptr(W_packed, "W_packed"),
+                                        _ptr(masks_packed, "masks_packed"), _ptr(Wo_packed, "Wo_packed"),
+                                        _ptr(hidden, "hidden"), _ptr(y, "y"), _ptr(workspace, "workspace"),
+                                        ws_bytes, _stream(x)))
+    return y, hidden
 
 
 def mglu_forward_bool(desc, x, W, masks, out=None, workspace=None):

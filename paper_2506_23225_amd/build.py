@@ -12,7 +12,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libmglu.so")
-SOURCES = ["mglu_api.hip", "mglu_pack.hip", "mglu_stream.hip", "mglu_prefill.hip"]
+SOURCES = ["mglu_api.hip", "mglu_pack.hip", "mglu_stream.hip", "mglu_prefill.hip", "mglu_route.hip"]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wextra",
     "-Wno-unused-command-line-argument",

@@ -167,9 +167,9 @@ size_t mglu_workspace_bytes(const mglu_desc *desc)
     return 0;
 }
 
-mglu_status mglu_forward(const mglu_desc *desc, const void *x_dev, const void *W_packed_dev,
-                         const void *masks_packed_dev, void *out_dev, void *workspace_dev,
-                         size_t workspace_bytes, void *stream)
+mglu_status mglu_forward_variant(const mglu_desc *desc, const mglu_variant *variant, const void *x_dev,
+                                 const void *W_packed_dev, const void *masks_packed_dev, void *out_dev,
+                                 void *workspace_dev, size_t workspace_bytes, void *stream)
 {
     MGLU_TRY(check_forward(desc, true));
     MGLU_TRY(check_ptr(x_dev, "x_dev"));
@@ -178,12 +178,28 @@ mglu_status mglu_forward(const mglu_desc *desc, const void *x_dev, const void *W
     MGLU_TRY(check_ptr(out_dev, "out_dev"));
     (void)workspace_dev;
     (void)workspace_bytes;
+    int gate_fn = 0, mask_use = 0;
+    const float *route = nullptr;
+    if (variant) {
+        if (variant->gate < MGLU_GATE_SWISH || variant->gate > MGLU_GATE_RELU)
+            return fail(MGLU_ERR_INVALID_ARG, "variant->gate %d is not a mglu_gate_fn", (int)variant->gate);
+        if (variant->mask_use < MGLU_MASK_BOTH || variant->mask_use > MGLU_MASK_NONE)
+            return fail(MGLU_ERR_INVALID_ARG, "variant->mask_use %d is not a mglu_mask_use", (int)variant->mask_use);
+        if (variant->route_weights_dev && (reinterpret_cast<uintptr_t>(variant->route_weights_dev) & 3u))
+            return fail(MGLU_ERR_INVALID_ARG, "variant->route_weights_dev is not 4-byte aligned");
+        gate_fn = (int)variant->gate;
+        mask_use = (int)variant->mask_use;
+        route = variant->route_weights_dev;
+    }
     if (desc->dtype == MGLU_BF16 && desc->tokens > kStreamMaxTokens) {
         mglu::PrefillParams pp = prefill_params(desc);
         pp.x = x_dev;
         pp.w = W_packed_dev;
         pp.m = static_cast<const uint32_t *>(masks_packed_dev);
         pp.out = out_dev;
+        pp.gate_fn = gate_fn;
+        pp.mask_use = mask_use;
+        pp.route = route;
         return hip_result(mglu::launch_prefill(pp, mglu::kModeMglu, static_cast<hipStream_t>(stream)),
                           "mglu_forward (prefill) launch");
     }
@@ -192,8 +208,88 @@ mglu_status mglu_forward(const mglu_desc *desc, const void *x_dev, const void *W
     p.w = W_packed_dev;
     p.m = static_cast<const uint32_t *>(masks_packed_dev);
     p.out = out_dev;
+    p.gate_fn = gate_fn;
+    p.mask_use = mask_use;
+    p.route = route;
     return hip_result(mglu::launch_stream(p, desc->dtype == MGLU_F32, mglu::kModeMglu, static_cast<hipStream_t>(stream)),
                       "mglu_forward launch");
+}
+
+mglu_status mglu_forward(const mglu_desc *desc, const void *x_dev, const void *W_packed_dev,
+                         const void *masks_packed_dev, void *out_dev, void *workspace_dev,
+                         size_t workspace_bytes, void *stream)
+{
+    return mglu_forward_variant(desc, nullptr, x_dev, W_packed_dev, masks_packed_dev, out_dev, workspace_dev,
+                                workspace_bytes, stream);
+}
+
+mglu_status mglu_route_topk(const mglu_desc *desc, const void *x_dev, const void *Wr_dev, int k,
+                            float *weights_dev, void *stream)
+{
+    if (!desc) return fail(MGLU_ERR_INVALID_ARG, "descriptor is NULL");
+    if (desc->dtype != MGLU_F32 && desc->dtype != MGLU_BF16)
+        return fail(MGLU_ERR_INVALID_ARG, "dtype %d is neither MGLU_F32 nor MGLU_BF16", (int)desc->dtype);
+    if (desc->tokens < 1 || desc->d_model < 1)
+        return fail(MGLU_ERR_INVALID_ARG, "tokens=%d and d_model=%d must be >= 1", desc->tokens, desc->d_model);
+    if (desc->n_masks < 1) return fail(MGLU_ERR_INVALID_ARG, "n_masks=%d must be >= 1", desc->n_masks);
+    if (desc->n_masks > 8) return fail(MGLU_ERR_UNSUPPORTED, "n_masks=%d: at most 8 masks are supported", desc->n_masks);
+    if (k < 1 || k > desc->n_masks) return fail(MGLU_ERR_INVALID_ARG, "k=%d must be in [1, n_masks=%d]", k, desc->n_masks);
+    MGLU_TRY(check_ptr(x_dev, "x_dev"));
+    MGLU_TRY(check_ptr(Wr_dev, "Wr_dev"));
+    MGLU_TRY(check_ptr(weights_dev, "weights_dev"));
+    mglu::RouteParams rp = {};
+    rp.x = x_dev;
+    rp.wr = Wr_dev;
+    rp.weights = weights_dev;
+    rp.T = desc->tokens;
+    rp.h = desc->d_model;
+    rp.n_masks = desc->n_masks;
+    rp.k = k;
+    return hip_result(mglu::launch_route_topk(rp, desc->dtype == MGLU_F32, static_cast<hipStream_t>(stream)),
+                      "mglu_route_topk launch");
+}
+
+mglu_status mglu_linear_forward(const mglu_desc *desc, const void *a_dev, const void *W_packed_dev,
+                                void *out_dev, void *workspace_dev, size_t workspace_bytes, void *stream)
+{
+    MGLU_TRY(check_forward(desc, false));
+    MGLU_TRY(check_ptr(a_dev, "a_dev"));
+    MGLU_TRY(check_ptr(W_packed_dev, "W_packed_dev"));
+    MGLU_TRY(check_ptr(out_dev, "out_dev"));
+    (void)workspace_dev;
+    (void)workspace_bytes;
+    if (desc->dtype == MGLU_BF16 && desc->tokens > kStreamMaxTokens) {
+        mglu::PrefillParams pp = prefill_params(desc);
+        pp.x = a_dev;
+        pp.w = W_packed_dev;
+        pp.out = out_dev;
+        return hip_result(mglu::launch_prefill(pp, mglu::kModeLinear, static_cast<hipStream_t>(stream)),
+                          "mglu_linear_forward (prefill) launch");
+    }
+    mglu::StreamParams p = stream_params(desc);
+    p.x = a_dev;
+    p.w = W_packed_dev;
+    p.out = out_dev;
+    return hip_result(mglu::launch_stream(p, desc->dtype == MGLU_F32, mglu::kModeLinear, static_cast<hipStream_t>(stream)),
+                      "mglu_linear_forward launch");
+}
+
+mglu_status mglu_ffn_forward(const mglu_desc *desc, const mglu_variant *variant, const void *x_dev,
+                             const void *W_packed_dev, const void *masks_packed_dev,
+                             const void *Wo_packed_dev, void *hidden_dev, void *y_dev,
+                             void *workspace_dev, size_t workspace_bytes, void *stream)
+{
+    MGLU_TRY(check_forward(desc, true));
+    MGLU_TRY(check_ptr(hidden_dev, "hidden_dev"));
+    MGLU_TRY(check_ptr(Wo_packed_dev, "Wo_packed_dev"));
+    MGLU_TRY(check_ptr(y_dev, "y_dev"));
+    mglu_desc down = *desc;        // the output projection reduces over d_ff and produces d_model columns
+    down.d_model = desc->d_ff;
+    down.d_ff = desc->d_model;
+    MGLU_TRY(check_forward(&down, false));
+    MGLU_TRY(mglu_forward_variant(desc, variant, x_dev, W_packed_dev, masks_packed_dev, hidden_dev, workspace_dev,
+                                  workspace_bytes, stream));
+    return mglu_linear_forward(&down, hidden_dev, Wo_packed_dev, y_dev, workspace_dev, workspace_bytes, stream);
 }
 
 size_t mglu_forward_bool_workspace_bytes(const mglu_desc *desc)

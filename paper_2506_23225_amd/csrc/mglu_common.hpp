@@ -136,9 +136,28 @@ struct F32Traits {
 
 // ---- what a launch computes ---------------------------------------------------------------
 enum Mode {
-    kModeMglu = 0,         // out = sum_i swish(gate_i) * value_i            (Eq. 3)
+    kModeMglu = 0,         // out = sum_i G_i g(gate_i) * value_i            (Eq. 3 and its appendix variants)
     kModeProjections = 1,  // t, gate_i, value_i in fp32                      (Alg. 1's z)
-    kModeSwiglu = 2        // out = swish(x Wg) * (x Wv), two weight streams  (Eq. 1)
+    kModeSwiglu = 2,       // out = swish(x Wg) * (x Wv), two weight streams  (Eq. 1)
+    kModeLinear = 3        // out = x W, no masks, no activation              (output projection W_o)
+};
+
+// accumulator sets a mode keeps per output tile
+__host__ __device__ constexpr int sets_of(int mode, int nmp)
+{
+    return mode == kModeSwiglu ? 2 : mode == kModeLinear ? 1 : 1 + nmp;
+}
+
+// What the fused epilogue applies to the reduced sums (appendix of the paper):
+//   gate_fn   0 Swish, 1 GELU (exact Gaussian CDF), 2 ReLU          ("Other Activation Functions")
+//   mask_use  bit 0: the gate branch is dense (x W), bit 1: the value branch is dense
+//             ("Partial Mask Ablation": 1 no gate mask, 2 no value mask, 3 no masks)
+//   route     null, or fp32 [tokens][n_masks] weights G(x)_i of the Top-K routed form
+struct EpilogueParams {
+    int n_masks;
+    int gate_fn;
+    int mask_use;
+    const float *route;
 };
 
 // Sign-flip form of the complement trick (Alg. 1 writes s_i and t - s_i): with
@@ -149,5 +168,28 @@ enum Mode {
 // is not exactly sign-symmetric), so value_i is then a few ulp of t instead of exactly 0.
 __device__ __forceinline__ float gate_of(float t, float dsum) { return 0.5f * (t - dsum); }
 __device__ __forceinline__ float value_of(float t, float dsum) { return 0.5f * (t + dsum); }
+
+__device__ __forceinline__ float gate_fn_apply(int gate_fn, float z)
+{
+    if (gate_fn == 1) return 0.5f * z * (1.0f + erff(z * 0.70710678118654752f));
+    if (gate_fn == 2) return fmaxf(z, 0.0f);
+    return swish(z);
+}
+
+// One output element of the layer from its reduced sums: t and dsum[0 .. n_masks).
+template <int NMP>
+__device__ __forceinline__ float mglu_mix(const EpilogueParams &e, long tok, float t, const float (&dsum)[NMP])
+{
+    float sum = 0.f;
+#pragma unroll
+    for (int i = 0; i < NMP; ++i) {
+        if (i >= e.n_masks) break;
+        const float gate = (e.mask_use & 1) ? t : gate_of(t, dsum[i]);
+        const float value = (e.mask_use & 2) ? t : value_of(t, dsum[i]);
+        const float term = gate_fn_apply(e.gate_fn, gate) * value;
+        sum += e.route ? e.route[tok * e.n_masks + i] * term : term;
+    }
+    return sum;
+}
 
 }  // namespace mglu

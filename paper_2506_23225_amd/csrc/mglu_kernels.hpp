@@ -17,6 +17,9 @@ struct StreamParams {
     int T, h, d, n_masks;
     int NB;               // column blocks  = ceil(d / 16)
     int NC;               // reduction chunks = ceil(h / 128)
+    int gate_fn;          // epilogue variant: see EpilogueParams
+    int mask_use;
+    const float *route;   // [T][n_masks] route weights, may be null
 };
 
 struct PrefillParams {
@@ -29,6 +32,16 @@ struct PrefillParams {
     int NB, NC;
     int tiles_m, tiles_n; // filled in by the launcher
     int group_m;          // token tiles per L2 patch
+    int gate_fn;          // epilogue variant: see EpilogueParams
+    int mask_use;
+    const float *route;   // [T][n_masks] route weights, may be null
+};
+
+struct RouteParams {
+    const void *x;        // [T][h]
+    const void *wr;       // [h][n_masks], same element type as x
+    float *weights;       // [T][n_masks]
+    int T, h, n_masks, k;
 };
 
 struct PackParams {
@@ -44,6 +57,8 @@ int stream_max_token_blocks(int nmp, bool is_f32);
 hipError_t launch_stream_read(const void *buf, size_t bytes, uint32_t *sink, hipStream_t stream);
 
 hipError_t launch_prefill(const PrefillParams &p, int mode, hipStream_t stream);
+
+hipError_t launch_route_topk(const RouteParams &p, bool is_f32, hipStream_t stream);
 
 hipError_t launch_pack_weights(const PackParams &p, bool is_f32, hipStream_t stream);
 hipError_t launch_pack_masks(const PackParams &p, bool is_f32, hipStream_t stream);

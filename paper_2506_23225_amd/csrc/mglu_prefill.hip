@@ -53,7 +53,7 @@ void prefill_kernel(PrefillParams p)
 {
     typedef Bf16Traits Tr;
     typedef Tr::frag frag;
-    constexpr int SETS = (MODE == kModeSwiglu) ? 2 : 1 + NMP;
+    constexpr int SETS = sets_of(MODE, NMP);
     constexpr int AR = 4;                       // ring entries (one per tile of a chunk)
     constexpr long CHUNK_BYTES = (long)kColBlock * kChunkK * 2;
     constexpr int XPIECES = TB * 4 / kPrefillWaves;  // x fragments each wavefront stages per chunk
@@ -149,7 +149,7 @@ void prefill_kernel(PrefillParams p)
         }
     };
     auto load_masks = [&](int kc, int slot) __attribute__((always_inline)) {
-        if constexpr (MODE != kModeSwiglu) {
+        if constexpr (MODE != kModeSwiglu && MODE != kModeLinear) {
 #pragma unroll
             for (int cb = 0; cb < CB; ++cb) {
                 const uint32_t *mp =
@@ -229,7 +229,7 @@ void prefill_kernel(PrefillParams p)
                 var[0][cb] = aw[t][cb];
                 if constexpr (MODE == kModeSwiglu) {
                     var[1][cb] = aw2[t][cb];
-                } else {
+                } else if constexpr (MODE != kModeLinear) {
 #pragma unroll
                     for (int i = 0; i < NMP; ++i) var[1 + i][cb] = Tr::template flip<NMP>(aw[t][cb], mk[MS][cb], t, i);
                 }
@@ -278,21 +278,19 @@ void prefill_kernel(PrefillParams p)
         for (int tb = 0; tb < TB; ++tb) {
             const long tok = (long)tok0 + 16 * tb + r;
             if (tok >= p.T) continue;
+            const EpilogueParams ep = {p.n_masks, p.gate_fn, p.mask_use, p.route};
             f32x4 y;
 #pragma unroll
             for (int c = 0; c < 4; ++c) {
                 if constexpr (MODE == kModeSwiglu) {
                     y[c] = swish(acc[0][cb][tb][c]) * acc[1][cb][tb][c];
+                } else if constexpr (MODE == kModeLinear) {
+                    y[c] = acc[0][cb][tb][c];
                 } else {
-                    const float t = acc[0][cb][tb][c];
-                    float sum = 0.f;
+                    float ds[NMP];
 #pragma unroll
-                    for (int i = 0; i < NMP; ++i) {
-                        if (i >= p.n_masks) break;
-                        const float ds = acc[1 + i][cb][tb][c];
-                        sum += swish(gate_of(t, ds)) * value_of(t, ds);
-                    }
-                    y[c] = sum;
+                    for (int i = 0; i < NMP; ++i) ds[i] = acc[1 + i][cb][tb][c];
+                    y[c] = mglu_mix<NMP>(ep, tok, acc[0][cb][tb][c], ds);
                 }
             }
             const long o = tok * p.d + j0;
@@ -328,6 +326,7 @@ static hipError_t launch_prefill_one(PrefillParams p, hipStream_t stream)
 hipError_t launch_prefill(const PrefillParams &p, int mode, hipStream_t stream)
 {
     if (mode == kModeSwiglu) return launch_prefill_one<1, 2, 8, kModeSwiglu, 1>(p, stream);
+    if (mode == kModeLinear) return launch_prefill_one<1, 2, 8, kModeLinear, 2>(p, stream);
     switch (round_up_masks(p.n_masks)) {
     case 1: return launch_prefill_one<1, 2, 8, kModeMglu, 1>(p, stream);
     case 2: return launch_prefill_one<2, 1, 8, kModeMglu, 2>(p, stream);

@@ -64,8 +64,6 @@ __device__ __forceinline__ T stream_load(const T *p)
 #endif
 }
 
-__host__ __device__ constexpr int sets_of(int mode, int nmp) { return mode == kModeSwiglu ? 2 : 1 + nmp; }
-
 // Registers of one chunk in flight: W (or the two SwiGLU matrices) and the mask words.
 template <typename Tr, int NMP, int MODE>
 struct WChunk {
@@ -84,6 +82,8 @@ __device__ __forceinline__ void load_wchunk(WChunk<Tr, NMP, MODE> &c, const char
     if constexpr (MODE == kModeSwiglu) {
 #pragma unroll
         for (int t = 0; t < Tr::TILES; ++t) c.w2[t] = stream_load(reinterpret_cast<const frag *>(wp2 + t * 1024));
+    } else if constexpr (MODE == kModeLinear) {
+        (void)mp;
     } else if constexpr (NMP == 8) {
         u32x4 a = stream_load(reinterpret_cast<const u32x4 *>(mp));
         u32x4 b = stream_load(reinterpret_cast<const u32x4 *>(mp) + 1);
@@ -102,18 +102,21 @@ __device__ __forceinline__ void load_wchunk(WChunk<Tr, NMP, MODE> &c, const char
 }
 
 // One 32-k (bf16) / 16-k (fp32) tile: t += W x, dsum_i += flip_i(W) x for every token block.
+// `active` (uniform over the wavefront) has bit i set if mask i's sum is needed at all: with Top-K
+// route weights the masks no token of the block selected are skipped, operand preparation included.
 template <typename Tr, int NMP, int TB, int MODE>
 __device__ __forceinline__ void mma_tile(f32x4 (&acc)[sets_of(MODE, NMP)][TB], const WChunk<Tr, NMP, MODE> &c, int t,
-                                const typename Tr::frag (&xf)[TB])
+                                const typename Tr::frag (&xf)[TB], uint32_t active = ~0u)
 {
 #pragma unroll
     for (int tb = 0; tb < TB; ++tb) acc[0][tb] = Tr::mma(c.w[t], xf[tb], acc[0][tb]);
     if constexpr (MODE == kModeSwiglu) {
 #pragma unroll
         for (int tb = 0; tb < TB; ++tb) acc[1][tb] = Tr::mma(c.w2[t], xf[tb], acc[1][tb]);
-    } else {
+    } else if constexpr (MODE != kModeLinear) {
 #pragma unroll
         for (int i = 0; i < NMP; ++i) {
+            if (!((active >> i) & 1u)) continue;
             const typename Tr::frag wf = Tr::template flip<NMP>(c.w[t], c.m, t, i);
 #pragma unroll
             for (int tb = 0; tb < TB; ++tb) acc[1 + i][tb] = Tr::mma(wf, xf[tb], acc[1 + i][tb]);
@@ -150,21 +153,19 @@ __device__ __forceinline__ void epilogue(const StreamParams &p, const f32x4 (&ac
                 }
             }
         } else {
+            const EpilogueParams ep = {p.n_masks, p.gate_fn, p.mask_use, p.route};
             f32x4 y;
 #pragma unroll
             for (int c = 0; c < 4; ++c) {
                 if constexpr (MODE == kModeSwiglu) {
                     y[c] = swish(acc[0][tb][c]) * acc[1][tb][c];
+                } else if constexpr (MODE == kModeLinear) {
+                    y[c] = acc[0][tb][c];
                 } else {
-                    const float t = acc[0][tb][c];
-                    float sum = 0.f;
+                    float ds[NMP];
 #pragma unroll
-                    for (int i = 0; i < NMP; ++i) {
-                        if (i >= p.n_masks) break;
-                        const float ds = acc[1 + i][tb][c];
-                        sum += swish(gate_of(t, ds)) * value_of(t, ds);
-                    }
-                    y[c] = sum;
+                    for (int i = 0; i < NMP; ++i) ds[i] = acc[1 + i][tb][c];
+                    y[c] = mglu_mix<NMP>(ep, tok, acc[0][tb][c], ds);
                 }
             }
             if (full) {
@@ -216,12 +217,24 @@ __global__ __launch_bounds__(MGLU_STREAM_MAX_WAVES *kWave) void stream_resident_
         load_wchunk<Tr, NMP, MODE>(c, wbase + (long)kc * CHUNK_BYTES, w2base + (long)kc * CHUNK_BYTES,
                                    mbase + (long)kc * kWave * NMP);
     };
+    // Top-K routing: masks that no token of this block selected need no sum at all
+    uint32_t active = ~0u;
+    if constexpr (MODE == kModeMglu) {
+        if (p.route) {
+            active = 0u;
+#pragma unroll
+            for (int i = 0; i < NMP; ++i) {
+                const bool sel = i < p.n_masks && r < tc && p.route[(long)(tok0 + r) * p.n_masks + i] != 0.0f;
+                if (__builtin_amdgcn_ballot_w64(sel) != 0) active |= 1u << i;
+            }
+        }
+    }
     auto compute = [&](const chunk_t &c, int kc) __attribute__((always_inline)) {
 #pragma unroll
         for (int t = 0; t < Tr::TILES; ++t) {
             frag xf[1] = {frag{0, 0, 0, 0}};
             if (r < tc) xf[0] = lds_x[((kc * Tr::TILES + t) * 4 + q) * tc + r];
-            mma_tile<Tr, NMP, 1, MODE>(acc, c, t, xf);
+            mma_tile<Tr, NMP, 1, MODE>(acc, c, t, xf, active);
         }
     };
 
@@ -554,18 +567,20 @@ static hipError_t launch_nmp(const StreamParams &p, int nmp, const StreamPlan &p
 
 hipError_t launch_stream(const StreamParams &p, bool is_f32, int mode, hipStream_t stream)
 {
-    const int nmp = (mode == kModeSwiglu) ? 1 : round_up_masks(p.n_masks);
+    const int nmp = (mode == kModeSwiglu || mode == kModeLinear) ? 1 : round_up_masks(p.n_masks);
     const StreamPlan pl = plan_stream(p, is_f32, nmp, sets_of(mode, nmp));
     if (is_f32) {
         switch (mode) {
         case kModeMglu: return launch_nmp<F32Traits, kModeMglu>(p, nmp, pl, stream);
         case kModeProjections: return launch_nmp<F32Traits, kModeProjections>(p, nmp, pl, stream);
+        case kModeLinear: return launch_plan<F32Traits, 1, kModeLinear>(p, pl, stream);
         default: return launch_plan<F32Traits, 1, kModeSwiglu>(p, pl, stream);
         }
     }
     switch (mode) {
     case kModeMglu: return launch_nmp<Bf16Traits, kModeMglu>(p, nmp, pl, stream);
     case kModeProjections: return launch_nmp<Bf16Traits, kModeProjections>(p, nmp, pl, stream);
+    case kModeLinear: return launch_plan<Bf16Traits, 1, kModeLinear>(p, pl, stream);
     default: return launch_plan<Bf16Traits, 1, kModeSwiglu>(p, pl, stream);
     }
 }
