@@ -81,6 +81,35 @@ class Workload:
         Wp, Mp = self.ring[i % self.copies]
         self.api.mglu_forward(self.desc, self.x, Wp, Mp, out=self.out, workspace=self.ws)
 
+    # ---- widened rows: Top-K routed layer and the whole FFN block (layer + output projection) ----
+    def enable_routing(self, k):
+        """Route weights from the library's router on a seeded random W_r; routed_step then runs the routed layer."""
+        torch = self.torch
+        gen = torch.Generator(device="cuda:0").manual_seed(2)
+        Wr = (torch.randn(self.cfg["d_model"], self.cfg["n_masks"], generator=gen, device="cuda:0") * 0.1).to(self.x.dtype)
+        self.route = self.api.mglu_route_topk(self.desc, self.x, Wr, k)
+
+    def routed_step(self, i):
+        Wp, Mp = self.ring[i % self.copies]
+        self.api.mglu_forward_variant(self.desc, self.x, Wp, Mp, route_weights=self.route, out=self.out, workspace=self.ws)
+
+    def enable_ffn(self, ring_bytes=2 * LLC_BYTES):
+        torch = self.torch
+        T, h, d = self.cfg["tokens"], self.cfg["d_model"], self.cfg["d_ff"]
+        gen = torch.Generator(device="cuda:0").manual_seed(3)
+        Wo = (torch.randn(d, h, generator=gen, device="cuda:0") * 0.02).to(self.x.dtype)
+        self.down = self.api.make_desc(T, d, h, 1, self.x.dtype)
+        Wop = self.api.mglu_pack_weights(self.down, Wo)
+        self.wo_ring = [Wop] + [Wop.clone() for _ in range(self.copies - 1)]
+        self.y = torch.empty(T, h, dtype=self.x.dtype, device="cuda:0")
+        self.ffn_bytes = self.bytes + Wop.numel() + 2 * T * d + 2 * T * h   # + Wo, hidden in again, y out
+        self.ffn_flops = self.flops + 2 * T * d * h
+
+    def ffn_step(self, i):
+        Wp, Mp = self.ring[i % self.copies]
+        self.api.mglu_ffn_forward(self.desc, self.x, Wp, Mp, self.wo_ring[i % self.copies], hidden=self.out, y=self.y,
+                                  workspace=self.ws)
+
     def swiglu_step(self, i):
         Wg, Wv = self.swiglu_ring[i % len(self.swiglu_ring)]
         self.api.swiglu_forward(self.desc, self.x, Wg, Wv, out=self.out, workspace=self.ws)
@@ -270,6 +299,38 @@ def run_extras(torch, synth, args):
         out.append(rec)
         print("[bench] %-40s %9.4f ms  %8.1f GB/s (%.1f%% HBM)  %8.1f TFLOP/s (%.1f%% MFMA)  swiglu %9.4f ms"
               % (name, ms, rec["GBps"], 100 * rec["hbm_frac"], rec["TFLOPs"], 100 * rec["mfma_frac"], sw_ms),
+              file=sys.stderr, flush=True)
+        del w
+        torch.cuda.empty_cache()
+    out.extend(run_widened(torch, synth, only))
+    return out
+
+
+def run_widened(torch, synth, only):
+    """Rows beyond the up-projection itself: the Top-K routed layer and the whole FFN block."""
+    out = []
+    cases = [("routed top-2 of 8, decode_8b 4096x14336 T=1", synth.config("decode_8b", tokens=1), "routed", 200, 20),
+             ("routed top-2 of 8, large 8192x28672 T=1", synth.config("large", n_masks=8, tokens=1), "routed", 60, 6),
+             ("ffn (layer + output projection), decode_8b 4096x14336 n_m=8 T=1", synth.config("decode_8b", tokens=1), "ffn", 200, 20),
+             ("ffn (layer + output projection), prefill_8b 4096x14336 n_m=4 T=4096", synth.config("prefill_8b"), "ffn", 10, 2)]
+    for name, cfg, kind, steps, warmup in cases:
+        if only and not any(o in name for o in only):
+            continue
+        w = Workload(name, cfg, swiglu=False)
+        if kind == "routed":
+            w.enable_routing(2)
+            ms, wall_ms = time_steps(torch, w.routed_step, steps, warmup)
+            rec = summarize(w, ms, wall_ms, "hbm")
+            rec["note"] = "same bytes as the unrouted layer; route weights applied in the epilogue"
+        else:
+            w.enable_ffn()
+            ms, wall_ms = time_steps(torch, w.ffn_step, steps, warmup)
+            w.bytes, w.flops = w.ffn_bytes, w.ffn_flops
+            rec = summarize(w, ms, wall_ms, "hbm" if cfg["tokens"] <= 64 else "mfma")
+            rec["note"] = "two launches; bytes and FLOPs include the output projection"
+        out.append(rec)
+        print("[bench] %-62s %9.4f ms  %8.1f GB/s (%.1f%% HBM)  %8.1f TFLOP/s (%.1f%% MFMA)"
+              % (name, ms, rec["GBps"], 100 * rec["hbm_frac"], rec["TFLOPs"], 100 * rec["mfma_frac"]),
               file=sys.stderr, flush=True)
         del w
         torch.cuda.empty_cache()

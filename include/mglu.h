@@ -98,7 +98,9 @@ mglu_status mglu_pack_masks(const mglu_desc *desc, const uint8_t *masks_dev, voi
 
 /* ---- the per-token path (Eq. 3; Alg. 1) -------------------------------------------------- */
 
-/* Bytes of scratch mglu_forward needs for this descriptor (may be 0). */
+/* Bytes of scratch mglu_forward needs for this descriptor.  Every kernel of this version keeps its
+ * partial sums in registers and LDS, so this is 0 for every descriptor; the argument pair stays in
+ * the signatures so that a later version can ask for scratch without an interface change. */
 size_t mglu_workspace_bytes(const mglu_desc *desc);
 
 /* out[tokens][d_ff] = MGLU_{n_masks}(x), Eq. 3 with g = Swish.
@@ -107,10 +109,8 @@ size_t mglu_workspace_bytes(const mglu_desc *desc);
  *   masks_packed_dev from mglu_pack_masks with the same d_model, d_ff, n_masks, dtype
  *   out_dev          [tokens][d_ff], desc->dtype, fully overwritten (rounded once, to
  *                    nearest-even, after the sum over masks)
- *   workspace_dev    at least mglu_workspace_bytes(desc) bytes, may be NULL if that is 0.
- *                    Its contents need not be initialised, except that a workspace
- *                    used by the split reduction must have been zero-filled ONCE before
- *                    its first use (the kernels leave it zeroed again).
+ *   workspace_dev    at least mglu_workspace_bytes(desc) bytes, may be NULL if that is 0;
+ *                    contents need not be initialised and are not preserved.
  * The result is deterministic: the same inputs give the same bits on every call. */
 mglu_status mglu_forward(const mglu_desc *desc, const void *x_dev, const void *W_packed_dev,
                          const void *masks_packed_dev, void *out_dev,
@@ -155,8 +155,8 @@ typedef struct {
     /* Per-token route weights G(x)_i of the Top-K routed layer (appendix "Top-K Routing"):
      *   out = sum_i G(x)_i g(x (M_i*W)) * x ((1-M_i)*W).
      * dev, fp32 [tokens][n_masks], e.g. from mglu_route_topk; NULL means every weight is 1.
-     * In the decode path (tokens <= 16, x resident in LDS) a mask whose weight is 0 for every
-     * token of the call is skipped entirely -- no operand preparation, no MFMA. */
+     * Every mask's term is computed and then weighted (a weight of 0 drops it): all the masks'
+     * bits stream from memory whatever the selection, so skipping terms would save no traffic. */
     const float *route_weights_dev;
 } mglu_variant;
 

@@ -125,7 +125,7 @@ mglu::PackParams pack_params(const mglu_desc *d, const void *src, void *dst)
 
 extern "C" {
 
-int mglu_format_version(void) { return 1; }
+int mglu_format_version(void) { return 2; }
 
 size_t mglu_packed_weight_bytes(const mglu_desc *desc)
 {
@@ -191,6 +191,8 @@ mglu_status mglu_forward_variant(const mglu_desc *desc, const mglu_variant *vari
         mask_use = (int)variant->mask_use;
         route = variant->route_weights_dev;
     }
+    // the main form (Swish, both branches masked, no route weights) runs the kernels without the run-time choices
+    const int mode = (gate_fn != 0 || mask_use != 0 || route) ? mglu::kModeMgluVariant : mglu::kModeMglu;
     if (desc->dtype == MGLU_BF16 && desc->tokens > kStreamMaxTokens) {
         mglu::PrefillParams pp = prefill_params(desc);
         pp.x = x_dev;
@@ -200,7 +202,7 @@ mglu_status mglu_forward_variant(const mglu_desc *desc, const mglu_variant *vari
         pp.gate_fn = gate_fn;
         pp.mask_use = mask_use;
         pp.route = route;
-        return hip_result(mglu::launch_prefill(pp, mglu::kModeMglu, static_cast<hipStream_t>(stream)),
+        return hip_result(mglu::launch_prefill(pp, mode, static_cast<hipStream_t>(stream)),
                           "mglu_forward (prefill) launch");
     }
     mglu::StreamParams p = stream_params(desc);
@@ -211,7 +213,7 @@ mglu_status mglu_forward_variant(const mglu_desc *desc, const mglu_variant *vari
     p.gate_fn = gate_fn;
     p.mask_use = mask_use;
     p.route = route;
-    return hip_result(mglu::launch_stream(p, desc->dtype == MGLU_F32, mglu::kModeMglu, static_cast<hipStream_t>(stream)),
+    return hip_result(mglu::launch_stream(p, desc->dtype == MGLU_F32, mode, static_cast<hipStream_t>(stream)),
                       "mglu_forward launch");
 }
 

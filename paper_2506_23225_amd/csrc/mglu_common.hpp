@@ -16,6 +16,8 @@
 // v_mfma_f32_16x16x4_f32 (row = lane%16, k = lane/16, one per e).
 //
 //   masks  [jb][kc][lane<64][word<NMP]  uint32,  NMP = n_masks rounded up to 1,2,4,8
+//          (NMP = 8: [jb][kc][half<2][lane<64][word<4], word w of a lane = half w/4, word w%4, so
+//           that every 16-byte-per-lane load of a wavefront is one contiguous 1 KiB run)
 //
 // A lane's NMP words hold the NMP x 32 mask bits of the 32 weight elements that
 // lane holds in the chunk.  bf16: the elements form 16 register pairs
@@ -40,6 +42,12 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 
 __host__ __device__ constexpr int round_up_masks(int n) { return n <= 1 ? 1 : n <= 2 ? 2 : n <= 4 ? 4 : 8; }
 __host__ __device__ constexpr long ceil_div(long a, long b) { return (a + b - 1) / b; }
+
+// Byte offset of a lane's mask words inside a chunk's mask block, and the stride between its two
+// 16-byte halves when there are 8 masks.
+template <int NMP>
+__host__ __device__ constexpr uint32_t mask_lane_bytes(int lane) { return NMP == 8 ? lane * 16 : lane * NMP * 4; }
+constexpr uint32_t kMaskHalfBytes = kWave * 16;
 
 // ---- fp32 <-> bf16 ---------------------------------------------------------------------
 __device__ __forceinline__ float bf16_bits_to_f32(uint32_t b) { return __uint_as_float(b << 16); }
@@ -136,10 +144,13 @@ struct F32Traits {
 
 // ---- what a launch computes ---------------------------------------------------------------
 enum Mode {
-    kModeMglu = 0,         // out = sum_i G_i g(gate_i) * value_i            (Eq. 3 and its appendix variants)
+    kModeMglu = 0,         // out = sum_i swish(gate_i) * value_i             (Eq. 3)
     kModeProjections = 1,  // t, gate_i, value_i in fp32                      (Alg. 1's z)
     kModeSwiglu = 2,       // out = swish(x Wg) * (x Wv), two weight streams  (Eq. 1)
-    kModeLinear = 3        // out = x W, no masks, no activation              (output projection W_o)
+    kModeLinear = 3,       // out = x W, no masks, no activation              (output projection W_o)
+    kModeMgluVariant = 4   // out = sum_i G_i g(gate_i) * value_i with the gate function, the masked
+                           // branches and the route weights chosen at run time (appendix variants);
+                           // kept apart so that the main form's epilogue stays free of those choices
 };
 
 // accumulator sets a mode keeps per output tile

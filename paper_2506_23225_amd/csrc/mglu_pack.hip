@@ -82,9 +82,17 @@ __global__ __launch_bounds__(256) void pack_masks_kernel(PackParams p)
             }
         }
     }
-    uint32_t *dst = static_cast<uint32_t *>(p.dst) + gid * NMP;
+    // 16 bytes per lane per wavefront load: with 8 masks the lane's 8 words go to two 1 KiB halves
+    // of the chunk's mask block (words 0-3, then words 4-7), so each load is one contiguous run
+    if (NMP == 8) {
+        uint32_t *dst = static_cast<uint32_t *>(p.dst) + (gid / kWave) * (kWave * 8) + lane * 4;
 #pragma unroll
-    for (int w = 0; w < NMP; ++w) dst[w] = words[w];
+        for (int w = 0; w < NMP; ++w) dst[(w / 4) * (kWave * 4) + (w % 4)] = words[w];
+    } else {
+        uint32_t *dst = static_cast<uint32_t *>(p.dst) + gid * NMP;
+#pragma unroll
+        for (int w = 0; w < NMP; ++w) dst[w] = words[w];
+    }
 }
 
 hipError_t launch_pack_weights(const PackParams &p, bool is_f32, hipStream_t stream)

@@ -100,7 +100,7 @@ void prefill_kernel(PrefillParams p)
         w2base[cb] = static_cast<const char *>(p.w2) + jb * p.NC * CHUNK_BYTES;
         mbase[cb] = reinterpret_cast<const char *>(p.m) + jb * p.NC * (kWave * NMP * 4);
     }
-    const uint32_t lane_m = lane * (NMP * 4);
+    const uint32_t lane_m = mask_lane_bytes<NMP>(lane);
 
     f32x4 acc[SETS][CB][TB];
 #pragma unroll
@@ -155,7 +155,8 @@ void prefill_kernel(PrefillParams p)
                 const uint32_t *mp =
                     reinterpret_cast<const uint32_t *>(mbase[cb] + (long)kc * (kWave * NMP * 4) + lane_m);
                 if constexpr (NMP == 8) {
-                    u32x4 a = *reinterpret_cast<const u32x4 *>(mp), b = *(reinterpret_cast<const u32x4 *>(mp) + 1);
+                    u32x4 a = *reinterpret_cast<const u32x4 *>(mp);
+                    u32x4 b = *reinterpret_cast<const u32x4 *>(reinterpret_cast<const char *>(mp) + kMaskHalfBytes);
 #pragma unroll
                     for (int i = 0; i < 4; ++i) { mk[slot][cb][i] = a[i]; mk[slot][cb][4 + i] = b[i]; }
                 } else if constexpr (NMP == 4) {
@@ -278,7 +279,9 @@ void prefill_kernel(PrefillParams p)
         for (int tb = 0; tb < TB; ++tb) {
             const long tok = (long)tok0 + 16 * tb + r;
             if (tok >= p.T) continue;
-            const EpilogueParams ep = {p.n_masks, p.gate_fn, p.mask_use, p.route};
+            const EpilogueParams ep = MODE == kModeMgluVariant
+                                          ? EpilogueParams{p.n_masks, p.gate_fn, p.mask_use, p.route}
+                                          : EpilogueParams{p.n_masks, 0, 0, nullptr};
             f32x4 y;
 #pragma unroll
             for (int c = 0; c < 4; ++c) {
@@ -327,6 +330,14 @@ hipError_t launch_prefill(const PrefillParams &p, int mode, hipStream_t stream)
 {
     if (mode == kModeSwiglu) return launch_prefill_one<1, 2, 8, kModeSwiglu, 1>(p, stream);
     if (mode == kModeLinear) return launch_prefill_one<1, 2, 8, kModeLinear, 2>(p, stream);
+    if (mode == kModeMgluVariant) {
+        switch (round_up_masks(p.n_masks)) {
+        case 1: return launch_prefill_one<1, 2, 8, kModeMgluVariant, 1>(p, stream);
+        case 2: return launch_prefill_one<2, 1, 8, kModeMgluVariant, 2>(p, stream);
+        case 4: return launch_prefill_one<4, 1, MGLU_PREFILL_TB4, kModeMgluVariant, MGLU_PREFILL_AD4>(p, stream);
+        default: return launch_prefill_one<8, 1, 4, kModeMgluVariant, 2>(p, stream);
+        }
+    }
     switch (round_up_masks(p.n_masks)) {
     case 1: return launch_prefill_one<1, 2, 8, kModeMglu, 1>(p, stream);
     case 2: return launch_prefill_one<2, 1, 8, kModeMglu, 2>(p, stream);

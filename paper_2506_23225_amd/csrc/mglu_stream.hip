@@ -86,7 +86,7 @@ __device__ __forceinline__ void load_wchunk(WChunk<Tr, NMP, MODE> &c, const char
         (void)mp;
     } else if constexpr (NMP == 8) {
         u32x4 a = stream_load(reinterpret_cast<const u32x4 *>(mp));
-        u32x4 b = stream_load(reinterpret_cast<const u32x4 *>(mp) + 1);
+        u32x4 b = stream_load(reinterpret_cast<const u32x4 *>(reinterpret_cast<const char *>(mp) + kMaskHalfBytes));
 #pragma unroll
         for (int i = 0; i < 4; ++i) { c.m[i] = a[i]; c.m[4 + i] = b[i]; }
     } else if constexpr (NMP == 4) {
@@ -102,11 +102,9 @@ __device__ __forceinline__ void load_wchunk(WChunk<Tr, NMP, MODE> &c, const char
 }
 
 // One 32-k (bf16) / 16-k (fp32) tile: t += W x, dsum_i += flip_i(W) x for every token block.
-// `active` (uniform over the wavefront) has bit i set if mask i's sum is needed at all: with Top-K
-// route weights the masks no token of the block selected are skipped, operand preparation included.
 template <typename Tr, int NMP, int TB, int MODE>
 __device__ __forceinline__ void mma_tile(f32x4 (&acc)[sets_of(MODE, NMP)][TB], const WChunk<Tr, NMP, MODE> &c, int t,
-                                const typename Tr::frag (&xf)[TB], uint32_t active = ~0u)
+                                const typename Tr::frag (&xf)[TB])
 {
 #pragma unroll
     for (int tb = 0; tb < TB; ++tb) acc[0][tb] = Tr::mma(c.w[t], xf[tb], acc[0][tb]);
@@ -116,7 +114,6 @@ __device__ __forceinline__ void mma_tile(f32x4 (&acc)[sets_of(MODE, NMP)][TB], c
     } else if constexpr (MODE != kModeLinear) {
 #pragma unroll
         for (int i = 0; i < NMP; ++i) {
-            if (!((active >> i) & 1u)) continue;
             const typename Tr::frag wf = Tr::template flip<NMP>(c.w[t], c.m, t, i);
 #pragma unroll
             for (int tb = 0; tb < TB; ++tb) acc[1 + i][tb] = Tr::mma(wf, xf[tb], acc[1 + i][tb]);
@@ -153,7 +150,9 @@ __device__ __forceinline__ void epilogue(const StreamParams &p, const f32x4 (&ac
                 }
             }
         } else {
-            const EpilogueParams ep = {p.n_masks, p.gate_fn, p.mask_use, p.route};
+            const EpilogueParams ep = MODE == kModeMgluVariant
+                                          ? EpilogueParams{p.n_masks, p.gate_fn, p.mask_use, p.route}
+                                          : EpilogueParams{p.n_masks, 0, 0, nullptr};
             f32x4 y;
 #pragma unroll
             for (int c = 0; c < 4; ++c) {
@@ -202,7 +201,8 @@ __global__ __launch_bounds__(MGLU_STREAM_MAX_WAVES *kWave) void stream_resident_
 
     const char *wbase = static_cast<const char *>(p.w) + (long)jb * p.NC * CHUNK_BYTES + lane * 16;
     const char *w2base = static_cast<const char *>(p.w2) + (long)jb * p.NC * CHUNK_BYTES + lane * 16;
-    const uint32_t *mbase = p.m + ((long)jb * p.NC * kWave + lane) * NMP;
+    const uint32_t *mbase = reinterpret_cast<const uint32_t *>(
+        reinterpret_cast<const char *>(p.m + (long)jb * p.NC * kWave * NMP) + mask_lane_bytes<NMP>(lane));
 
     // LDS: [x fragments of this token block][hand-over area of the K-split reduction]
     frag *lds_x = reinterpret_cast<frag *>(lds);
@@ -217,24 +217,12 @@ __global__ __launch_bounds__(MGLU_STREAM_MAX_WAVES *kWave) void stream_resident_
         load_wchunk<Tr, NMP, MODE>(c, wbase + (long)kc * CHUNK_BYTES, w2base + (long)kc * CHUNK_BYTES,
                                    mbase + (long)kc * kWave * NMP);
     };
-    // Top-K routing: masks that no token of this block selected need no sum at all
-    uint32_t active = ~0u;
-    if constexpr (MODE == kModeMglu) {
-        if (p.route) {
-            active = 0u;
-#pragma unroll
-            for (int i = 0; i < NMP; ++i) {
-                const bool sel = i < p.n_masks && r < tc && p.route[(long)(tok0 + r) * p.n_masks + i] != 0.0f;
-                if (__builtin_amdgcn_ballot_w64(sel) != 0) active |= 1u << i;
-            }
-        }
-    }
     auto compute = [&](const chunk_t &c, int kc) __attribute__((always_inline)) {
 #pragma unroll
         for (int t = 0; t < Tr::TILES; ++t) {
             frag xf[1] = {frag{0, 0, 0, 0}};
             if (r < tc) xf[0] = lds_x[((kc * Tr::TILES + t) * 4 + q) * tc + r];
-            mma_tile<Tr, NMP, 1, MODE>(acc, c, t, xf, active);
+            mma_tile<Tr, NMP, 1, MODE>(acc, c, t, xf);
         }
     };
 
@@ -347,7 +335,8 @@ void stream_panel_kernel(StreamParams p)
 
     const char *wbase = static_cast<const char *>(p.w) + jbc * p.NC * CHUNK_BYTES + lane * 16;
     const char *w2base = static_cast<const char *>(p.w2) + jbc * p.NC * CHUNK_BYTES + lane * 16;
-    const uint32_t *mbase = p.m + (jbc * p.NC * kWave + lane) * NMP;
+    const uint32_t *mbase = reinterpret_cast<const uint32_t *>(
+        reinterpret_cast<const char *>(p.m + jbc * p.NC * kWave * NMP) + mask_lane_bytes<NMP>(lane));
 
     f32x4 acc[SETS][TB];
 #pragma unroll
@@ -572,6 +561,7 @@ hipError_t launch_stream(const StreamParams &p, bool is_f32, int mode, hipStream
     if (is_f32) {
         switch (mode) {
         case kModeMglu: return launch_nmp<F32Traits, kModeMglu>(p, nmp, pl, stream);
+        case kModeMgluVariant: return launch_nmp<F32Traits, kModeMgluVariant>(p, nmp, pl, stream);
         case kModeProjections: return launch_nmp<F32Traits, kModeProjections>(p, nmp, pl, stream);
         case kModeLinear: return launch_plan<F32Traits, 1, kModeLinear>(p, pl, stream);
         default: return launch_plan<F32Traits, 1, kModeSwiglu>(p, pl, stream);
@@ -579,6 +569,7 @@ hipError_t launch_stream(const StreamParams &p, bool is_f32, int mode, hipStream
     }
     switch (mode) {
     case kModeMglu: return launch_nmp<Bf16Traits, kModeMglu>(p, nmp, pl, stream);
+    case kModeMgluVariant: return launch_nmp<Bf16Traits, kModeMgluVariant>(p, nmp, pl, stream);
     case kModeProjections: return launch_nmp<Bf16Traits, kModeProjections>(p, nmp, pl, stream);
     case kModeLinear: return launch_plan<Bf16Traits, 1, kModeLinear>(p, pl, stream);
     default: return launch_plan<Bf16Traits, 1, kModeSwiglu>(p, pl, stream);
