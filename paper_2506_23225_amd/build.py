@@ -18,6 +18,8 @@ FLAGS = [
     "-Wno-unused-command-line-argument",
     # packed-fp32 instructions are kept out of the generated code on purpose
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+    # leading kernel arguments arrive in scalar registers instead of being loaded by the kernel
+    "-mllvm", "-amdgpu-kernarg-preload-count=16",
 ]
 
 

@@ -34,8 +34,8 @@
 #ifndef MGLU_STREAM_MAX_WAVES
 #define MGLU_STREAM_MAX_WAVES 4   // resident kernel: wavefronts per workgroup = K-split ways
 #endif
-#ifndef MGLU_STREAM_PREFETCH
-#define MGLU_STREAM_PREFETCH 1    // chunks of loads in flight per wavefront ahead of the multiply
+#ifndef MGLU_STREAM_RING
+#define MGLU_STREAM_RING 2        // resident kernel: chunks of W a wavefront keeps in flight
 #endif
 #ifndef MGLU_STREAM_NONTEMPORAL
 #define MGLU_STREAM_NONTEMPORAL 1 // W and the masks are read once per call: mark the loads streaming
@@ -53,6 +53,19 @@
 #define MGLU_PANEL_OCCUPANCY(SETS_X_TB) __attribute__((amdgpu_waves_per_eu(2, (SETS_X_TB) > 12 ? 2 : 8)))
 
 namespace mglu {
+
+// Resident kernel: x fragments each thread copies per group (a power of two), and the LDS x area
+// rounded up to whole groups of the workgroup's 64 << nw_shift threads (so that every copy is
+// unconditional).  Shifts only: this runs at the start of every workgroup.
+constexpr int kResidentXGroupShift = 2;
+constexpr int kResidentXGroup = 1 << kResidentXGroupShift;
+// log2 of the rows per fragment group in the LDS copy of x: the token count rounded up to a power of two
+__host__ __device__ constexpr int resident_row_shift(int tc) { return tc <= 1 ? 0 : tc <= 2 ? 1 : tc <= 4 ? 2 : tc <= 8 ? 3 : 4; }
+__host__ __device__ constexpr int resident_x_frags_padded(int x_frags, int nw_shift)
+{
+    const int sh = kResidentXGroupShift + nw_shift + 6;
+    return ((x_frags + (1 << sh) - 1) >> sh) << sh;
+}
 
 template <typename T>
 __device__ __forceinline__ T stream_load(const T *p)
@@ -182,9 +195,21 @@ __device__ __forceinline__ void epilogue(const StreamParams &p, const f32x4 (&ac
 // Resident kernel: workgroup (jb, tg) owns columns [16 jb, 16 jb + 16) for the token block tg of
 // up to 16 tokens; its nw wavefronts take chunks kc = wave, wave + nw, ...
 // ================================================================================================
-template <typename Tr, int NMP, int MODE, int PF>
-__global__ __launch_bounds__(MGLU_STREAM_MAX_WAVES *kWave) void stream_resident_kernel(StreamParams p)
+// The arguments are passed one by one, the ones the first loads depend on first: the leading
+// ones are delivered in scalar registers when the wavefront starts (kernel-argument preload,
+// switched on in the build flags), which takes one memory round trip off the start of every
+// workgroup.
+template <typename Tr, int NMP, int MODE, int R>
+__global__ __launch_bounds__(MGLU_STREAM_MAX_WAVES *kWave) void stream_resident_kernel(
+    const void *a_w, const uint32_t *a_m, const void *a_x, int a_NC, int a_T, int a_h, int a_d, void *a_out,
+    int a_nw_shift, int a_n_masks, int a_NB, const void *a_w2, float *a_proj_t, float *a_proj_gate, float *a_proj_value,
+    int a_gate_fn, int a_mask_use, const float *a_route)
 {
+    StreamParams p;
+    p.x = a_x; p.w = a_w; p.w2 = a_w2; p.m = a_m; p.out = a_out;
+    p.proj_t = a_proj_t; p.proj_gate = a_proj_gate; p.proj_value = a_proj_value;
+    p.T = a_T; p.h = a_h; p.d = a_d; p.n_masks = a_n_masks; p.NB = a_NB; p.NC = a_NC;
+    p.gate_fn = a_gate_fn; p.mask_use = a_mask_use; p.route = a_route;
     constexpr int SETS = sets_of(MODE, NMP);
     constexpr long CHUNK_BYTES = (long)kColBlock * kChunkK * Tr::ELEM_BYTES;
     typedef typename Tr::frag frag;
@@ -193,7 +218,7 @@ __global__ __launch_bounds__(MGLU_STREAM_MAX_WAVES *kWave) void stream_resident_
 
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
-    const int nw = blockDim.x >> 6;
+    const int nw = 1 << a_nw_shift;      // wavefronts of this workgroup (= blockDim.x / 64), a power of two
     const int r = lane & 15, q = lane >> 4;
     const int jb = blockIdx.x;
     const int tok0 = blockIdx.y * 16;
@@ -204,10 +229,12 @@ __global__ __launch_bounds__(MGLU_STREAM_MAX_WAVES *kWave) void stream_resident_
     const uint32_t *mbase = reinterpret_cast<const uint32_t *>(
         reinterpret_cast<const char *>(p.m + (long)jb * p.NC * kWave * NMP) + mask_lane_bytes<NMP>(lane));
 
-    // LDS: [x fragments of this token block][hand-over area of the K-split reduction]
+    // LDS: [x fragments of this token block][hand-over area of the K-split reduction].  A fragment
+    // group g (LANE_K consecutive k) holds 2^tsh >= tc rows, so positions split with shifts only.
     frag *lds_x = reinterpret_cast<frag *>(lds);
-    const int x_frags = p.NC * Tr::TILES * 4 * tc;
-    f32x4 *lds_red = lds + x_frags;
+    const int tsh = resident_row_shift(tc);
+    const int x_frags = (p.NC * Tr::TILES * 4) << tsh;
+    f32x4 *lds_red = lds + resident_x_frags_padded(x_frags, a_nw_shift);
 
     f32x4 acc[SETS][1];
 #pragma unroll
@@ -221,67 +248,73 @@ __global__ __launch_bounds__(MGLU_STREAM_MAX_WAVES *kWave) void stream_resident_
 #pragma unroll
         for (int t = 0; t < Tr::TILES; ++t) {
             frag xf[1] = {frag{0, 0, 0, 0}};
-            if (r < tc) xf[0] = lds_x[((kc * Tr::TILES + t) * 4 + q) * tc + r];
+            if (r < tc) xf[0] = lds_x[((((kc * Tr::TILES + t) * 4 + q)) << tsh) + r];
             mma_tile<Tr, NMP, 1, MODE>(acc, c, t, xf);
         }
     };
 
-    // ---- The ring of PF + 1 register buffers is indexed at compile time, so the steady-state loop is
-    //      unrolled by PF + 1; inside it every load is unconditional, which lets the compiler wait
-    //      for exactly the chunk it multiplies. ----
-    const int n_my = (p.NC - wave + nw - 1) / nw;  // chunks this wavefront owns (NC >= nw, so >= 1)
+    // ---- A ring of R register buffers, indexed at compile time.  All R are loaded before anything
+    //      else waits, so a wavefront that owns at most R chunks has its whole share of W in flight
+    //      at once; otherwise a buffer is refilled right after it has been multiplied.  In the
+    //      steady-state loop every load is unconditional, which lets the compiler wait for exactly
+    //      the chunk it multiplies. ----
+    const int n_my = (p.NC - wave + nw - 1) >> a_nw_shift;  // chunks this wavefront owns (NC >= nw, so >= 1)
     auto kc_of = [&](int i) __attribute__((always_inline)) { return wave + i * nw; };
-    chunk_t buf[PF + 1];
+    chunk_t buf[R];
     {
-        // Copy this token block's x into LDS in fragment order: fragment f = g * tc + row holds
-        // x[tok0 + row][g * LANE_K .. + LANE_K), zero beyond d_model.  The first group of x loads
-        // is issued before the first W loads and, hitting L2, returns before them.
-        constexpr int XG = 4;  // fragments per thread per group
-        const int nthr = blockDim.x;
+        // Copy this token block's x into LDS in fragment order: fragment f = (g << tsh) + row holds
+        // x[tok0 + row][g * LANE_K .. + LANE_K), zero beyond d_model (rows >= tc repeat the last row).  The first group of x loads
+        // is issued before the W loads and, hitting L2, returns before them.  Loads and stores are
+        // unconditional (indices clamped, the LDS area padded to whole groups): a load whose only
+        // use sat under a condition would be moved behind the W loads and wait for all of them.
+        const int nthr = nw * kWave;
         auto x_load = [&](int f) __attribute__((always_inline)) {
             const int fc = min(f, x_frags - 1);  // clamped: the load is always in bounds
-            const int row = fc % tc, g = fc / tc;
+            const int row = min(fc & ((1 << tsh) - 1), tc - 1), g = fc >> tsh;
             const long k0 = min((long)g * Tr::LANE_K, (long)p.h - Tr::LANE_K);
             return *reinterpret_cast<const frag *>(static_cast<const char *>(p.x) +
                                                    ((long)(tok0 + row) * p.h + k0) * Tr::ELEM_BYTES);
         };
         auto x_store = [&](int f, frag v) __attribute__((always_inline)) {
-            if (f < x_frags) {
-                if ((long)(f / tc) * Tr::LANE_K >= p.h) v = frag{0, 0, 0, 0};
-                lds_x[f] = v;
-            }
+            if ((f >> tsh) * Tr::LANE_K >= p.h) v = frag{0, 0, 0, 0};
+            lds_x[f] = v;
         };
-        frag xv[XG];
+        frag xv[kResidentXGroup];
 #pragma unroll
-        for (int b = 0; b < XG; ++b) xv[b] = x_load(threadIdx.x + b * nthr);
+        for (int b = 0; b < kResidentXGroup; ++b) xv[b] = x_load(threadIdx.x + b * nthr);
 #pragma unroll
-        for (int s = 0; s < PF; ++s) load_chunk(buf[s], kc_of(min(s, n_my - 1)));
+        for (int s = 0; s < R; ++s) load_chunk(buf[s], kc_of(min(s, n_my - 1)));
+        __builtin_amdgcn_sched_barrier(0);  // every load above is issued before the first wait below
 #pragma unroll
-        for (int b = 0; b < XG; ++b) x_store(threadIdx.x + b * nthr, xv[b]);
-        for (int f0 = threadIdx.x + XG * nthr; f0 < x_frags; f0 += XG * nthr) {
+        for (int b = 0; b < kResidentXGroup; ++b) x_store(threadIdx.x + b * nthr, xv[b]);
+        for (int f0 = threadIdx.x + kResidentXGroup * nthr; f0 < x_frags; f0 += kResidentXGroup * nthr) {
 #pragma unroll
-            for (int b = 0; b < XG; ++b) xv[b] = x_load(f0 + b * nthr);
+            for (int b = 0; b < kResidentXGroup; ++b) xv[b] = x_load(f0 + b * nthr);
 #pragma unroll
-            for (int b = 0; b < XG; ++b) x_store(f0 + b * nthr, xv[b]);
+            for (int b = 0; b < kResidentXGroup; ++b) x_store(f0 + b * nthr, xv[b]);
         }
         __syncthreads();
     }
 
     int i0 = 0;
-    for (; i0 + 2 * PF < n_my; i0 += PF + 1) {  // every stage of the group has a chunk left to load
+    for (; i0 + 2 * R <= n_my; i0 += R) {  // every buffer of the ring has a chunk left to refill it
 #pragma unroll
-        for (int s = 0; s <= PF; ++s) {
-            load_chunk(buf[(s + PF) % (PF + 1)], kc_of(i0 + s + PF));
+        for (int s = 0; s < R; ++s) {
             compute(buf[s], kc_of(i0 + s));
+            load_chunk(buf[s], kc_of(i0 + R + s));
         }
     }
-    // tail: at most 2 PF chunks; i0 is a multiple of PF + 1, so chunk i0 + s sits in buf[s % (PF + 1)]
+    // tail: chunks i0 .. n_my - 1, fewer than 2 R; those below i0 + R are in the ring already
 #pragma unroll
-    for (int s = 0; s < 2 * PF; ++s) {
-        const int i = i0 + s;
-        if (i >= n_my) break;  // uniform over the wavefront
-        if (i + PF < n_my) load_chunk(buf[(s + PF) % (PF + 1)], kc_of(i + PF));
-        compute(buf[s % (PF + 1)], kc_of(i));
+    for (int s = 0; s < R; ++s) {
+        if (i0 + s >= n_my) break;  // uniform over the wavefront
+        compute(buf[s], kc_of(i0 + s));
+        if (i0 + R + s < n_my) load_chunk(buf[s], kc_of(i0 + R + s));
+    }
+#pragma unroll
+    for (int s = 0; s < R; ++s) {
+        if (i0 + R + s >= n_my) break;
+        compute(buf[s], kc_of(i0 + R + s));
     }
 
     // ---- combine the K split: wavefronts 1..nw-1 hand their sums to wavefront 0 through LDS,
@@ -465,7 +498,8 @@ struct StreamPlan {
     bool resident;
     bool wide;     // panel kernel: PanelWide (else PanelSplit)
     int tb;        // token blocks of 16 per workgroup
-    int nw;        // resident kernel: wavefronts per workgroup
+    int nw;        // resident kernel: wavefronts per workgroup, 1 << nw_shift
+    int nw_shift;
     size_t lds;
     dim3 grid, block;
 };
@@ -478,13 +512,17 @@ static StreamPlan plan_stream(const StreamParams &p, bool is_f32, int nmp, int s
     StreamPlan pl = {};
     // resident: one token block whose x rows (plus the reduction hand-over) fit the LDS budget
     const int tc = p.T < 16 ? p.T : 16;
-    int nw = p.NC < MGLU_STREAM_MAX_WAVES ? p.NC : MGLU_STREAM_MAX_WAVES;
+    // wavefronts that split K: a power of two, at most MGLU_STREAM_MAX_WAVES, and few enough that each owns two chunks
+    int nw_shift = 0;
+    while ((2 << nw_shift) <= MGLU_STREAM_MAX_WAVES && (4 << nw_shift) <= p.NC) ++nw_shift;
+    const int nw = 1 << nw_shift;
     const size_t red = nw > 1 ? (size_t)(nw - 1) * sets * 4 * tc * sizeof(f32x4) : 0;
-    const size_t xb = (size_t)p.NC * kChunkK * tc * elem;
+    const size_t xb = (size_t)resident_x_frags_padded((p.NC * tiles * 4) << resident_row_shift(tc), nw_shift) * 16;
     if (p.T <= 16 && xb + red <= kLdsBudget) {
         pl.resident = true;
         pl.tb = 1;
         pl.nw = nw;
+        pl.nw_shift = nw_shift;
         pl.lds = xb + red;
         pl.grid = dim3(p.NB, 1);
         pl.block = dim3(nw * kWave);
@@ -520,6 +558,14 @@ static hipError_t launch_kernel(K kern, const StreamParams &p, const StreamPlan 
     return hipGetLastError();
 }
 
+template <typename K>
+static hipError_t launch_resident(K kern, const StreamParams &p, const StreamPlan &pl, hipStream_t stream)
+{
+    hipLaunchKernelGGL(kern, pl.grid, pl.block, pl.lds, stream, p.w, p.m, p.x, p.NC, p.T, p.h, p.d, p.out,
+                       pl.nw_shift, p.n_masks, p.NB, p.w2, p.proj_t, p.proj_gate, p.proj_value, p.gate_fn, p.mask_use, p.route);
+    return hipGetLastError();
+}
+
 template <typename Tr, int NMP, int MODE, typename Shape>
 static hipError_t launch_panel(const StreamParams &p, const StreamPlan &pl, hipStream_t stream)
 {
@@ -538,7 +584,7 @@ static hipError_t launch_panel(const StreamParams &p, const StreamPlan &pl, hipS
 template <typename Tr, int NMP, int MODE>
 static hipError_t launch_plan(const StreamParams &p, const StreamPlan &pl, hipStream_t stream)
 {
-    if (pl.resident) return launch_kernel(stream_resident_kernel<Tr, NMP, MODE, MGLU_STREAM_PREFETCH>, p, pl, stream);
+    if (pl.resident) return launch_resident(stream_resident_kernel<Tr, NMP, MODE, MGLU_STREAM_RING>, p, pl, stream);
     return pl.wide ? launch_panel<Tr, NMP, MODE, PanelWide>(p, pl, stream)
                    : launch_panel<Tr, NMP, MODE, PanelSplit>(p, pl, stream);
 }
