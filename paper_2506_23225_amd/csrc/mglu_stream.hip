@@ -125,11 +125,15 @@ __device__ __forceinline__ void mma_tile(f32x4 (&acc)[sets_of(MODE, NMP)][TB], c
 #pragma unroll
         for (int tb = 0; tb < TB; ++tb) acc[1][tb] = Tr::mma(c.w2[t], xf[tb], acc[1][tb]);
     } else if constexpr (MODE != kModeLinear) {
+        // The flipped fragment of mask i + 1 is prepared in a second set of registers while the
+        // MFMAs of mask i run, so the vector ALU and the matrix pipe work at the same time.
+        typename Tr::frag wf[2];
+        wf[0] = Tr::template flip<NMP>(c.w[t], c.m, t, 0);
 #pragma unroll
         for (int i = 0; i < NMP; ++i) {
-            const typename Tr::frag wf = Tr::template flip<NMP>(c.w[t], c.m, t, i);
+            if (i + 1 < NMP) wf[(i + 1) & 1] = Tr::template flip<NMP>(c.w[t], c.m, t, i + 1);
 #pragma unroll
-            for (int tb = 0; tb < TB; ++tb) acc[1 + i][tb] = Tr::mma(wf, xf[tb], acc[1 + i][tb]);
+            for (int tb = 0; tb < TB; ++tb) acc[1 + i][tb] = Tr::mma(wf[i & 1], xf[tb], acc[1 + i][tb]);
         }
     }
 }
