@@ -187,9 +187,24 @@ __device__ __forceinline__ float gate_fn_apply(int gate_fn, float z)
     return swish(z);
 }
 
+// Route weights G(x)_i of one token (1 for every mask when the layer is not routed).  Loaded ahead
+// of the K loop where the latency of this small read would otherwise sit at the end of a workgroup.
+template <int NMP>
+__device__ __forceinline__ void route_weights(const EpilogueParams &e, long tok, bool valid, float (&rw)[NMP])
+{
+#pragma unroll
+    for (int i = 0; i < NMP; ++i) rw[i] = 1.0f;
+    if (e.route && valid) {
+#pragma unroll
+        for (int i = 0; i < NMP; ++i)
+            if (i < e.n_masks) rw[i] = e.route[tok * e.n_masks + i];
+    }
+}
+
 // One output element of the layer from its reduced sums: t and dsum[0 .. n_masks).
 template <int NMP>
-__device__ __forceinline__ float mglu_mix(const EpilogueParams &e, long tok, float t, const float (&dsum)[NMP])
+__device__ __forceinline__ float mglu_mix(const EpilogueParams &e, const float (&rw)[NMP], float t,
+                                          const float (&dsum)[NMP])
 {
     float sum = 0.f;
 #pragma unroll
@@ -198,7 +213,7 @@ __device__ __forceinline__ float mglu_mix(const EpilogueParams &e, long tok, flo
         const float gate = (e.mask_use & 1) ? t : gate_of(t, dsum[i]);
         const float value = (e.mask_use & 2) ? t : value_of(t, dsum[i]);
         const float term = gate_fn_apply(e.gate_fn, gate) * value;
-        sum += e.route ? e.route[tok * e.n_masks + i] * term : term;
+        sum += e.route ? rw[i] * term : term;
     }
     return sum;
 }

@@ -282,6 +282,8 @@ void prefill_kernel(PrefillParams p)
             const EpilogueParams ep = MODE == kModeMgluVariant
                                           ? EpilogueParams{p.n_masks, p.gate_fn, p.mask_use, p.route}
                                           : EpilogueParams{p.n_masks, 0, 0, nullptr};
+            float rw[NMP];
+            route_weights<NMP>(ep, tok, true, rw);
             f32x4 y;
 #pragma unroll
             for (int c = 0; c < 4; ++c) {
@@ -293,7 +295,7 @@ void prefill_kernel(PrefillParams p)
                     float ds[NMP];
 #pragma unroll
                     for (int i = 0; i < NMP; ++i) ds[i] = acc[1 + i][cb][tb][c];
-                    y[c] = mglu_mix<NMP>(ep, tok, acc[0][cb][tb][c], ds);
+                    y[c] = mglu_mix<NMP>(ep, rw, acc[0][cb][tb][c], ds);
                 }
             }
             const long o = tok * p.d + j0;

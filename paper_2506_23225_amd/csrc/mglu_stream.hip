@@ -139,9 +139,17 @@ __device__ __forceinline__ void mma_tile(f32x4 (&acc)[sets_of(MODE, NMP)][TB], c
 }
 
 // Epilogue on the reduced sums (Eq. 3): lane (r, q) holds token 16 tb + r, columns 4q .. 4q+3 of block jb.
+template <int MODE>
+__device__ __forceinline__ EpilogueParams epilogue_params(const StreamParams &p)
+{
+    return MODE == kModeMgluVariant ? EpilogueParams{p.n_masks, p.gate_fn, p.mask_use, p.route}
+                                    : EpilogueParams{p.n_masks, 0, 0, nullptr};
+}
+
+// rw: the route weights of this lane's token of every token block (see route_weights).
 template <typename Tr, int NMP, int TB, int MODE>
-__device__ __forceinline__ void epilogue(const StreamParams &p, const f32x4 (&acc)[sets_of(MODE, NMP)][TB], int jb, int tok0,
-                                int r, int q)
+__device__ __forceinline__ void epilogue(const StreamParams &p, const f32x4 (&acc)[sets_of(MODE, NMP)][TB],
+                                const float (&rw)[TB][NMP], int jb, int tok0, int r, int q)
 {
     const int j0 = jb * kColBlock + 4 * q;
     if (j0 >= p.d) return;
@@ -167,9 +175,7 @@ __device__ __forceinline__ void epilogue(const StreamParams &p, const f32x4 (&ac
                 }
             }
         } else {
-            const EpilogueParams ep = MODE == kModeMgluVariant
-                                          ? EpilogueParams{p.n_masks, p.gate_fn, p.mask_use, p.route}
-                                          : EpilogueParams{p.n_masks, 0, 0, nullptr};
+            const EpilogueParams ep = epilogue_params<MODE>(p);
             f32x4 y;
 #pragma unroll
             for (int c = 0; c < 4; ++c) {
@@ -181,7 +187,7 @@ __device__ __forceinline__ void epilogue(const StreamParams &p, const f32x4 (&ac
                     float ds[NMP];
 #pragma unroll
                     for (int i = 0; i < NMP; ++i) ds[i] = acc[1 + i][tb][c];
-                    y[c] = mglu_mix<NMP>(ep, tok, acc[0][tb][c], ds);
+                    y[c] = mglu_mix<NMP>(ep, rw[tb], acc[0][tb][c], ds);
                 }
             }
             if (full) {
@@ -243,6 +249,8 @@ __global__ __launch_bounds__(MGLU_STREAM_MAX_WAVES *kWave) void stream_resident_
     f32x4 acc[SETS][1];
 #pragma unroll
     for (int s = 0; s < SETS; ++s) acc[s][0] = f32x4{0.f, 0.f, 0.f, 0.f};
+    float rw[1][NMP];
+    route_weights<NMP>(epilogue_params<MODE>(p), tok0 + r, wave == 0 && r < tc, rw[0]);
 
     auto load_chunk = [&](chunk_t &c, int kc) __attribute__((always_inline)) {
         load_wchunk<Tr, NMP, MODE>(c, wbase + (long)kc * CHUNK_BYTES, w2base + (long)kc * CHUNK_BYTES,
@@ -335,7 +343,7 @@ __global__ __launch_bounds__(MGLU_STREAM_MAX_WAVES *kWave) void stream_resident_
                 for (int s = 0; s < SETS; ++s) acc[s][0] += lds_red[((w - 1) * SETS + s) * (4 * tc) + q * tc + r];
         }
     }
-    if (wave == 0) epilogue<Tr, NMP, 1, MODE>(p, acc, jb, tok0, r, q);
+    if (wave == 0) epilogue<Tr, NMP, 1, MODE>(p, acc, rw, jb, tok0, r, q);
 }
 
 // ================================================================================================
@@ -380,6 +388,10 @@ void stream_panel_kernel(StreamParams p)
     for (int st = 0; st < SETS; ++st)
 #pragma unroll
         for (int tb = 0; tb < TB; ++tb) acc[st][tb] = f32x4{0.f, 0.f, 0.f, 0.f};
+    float rw[TB][NMP];
+#pragma unroll
+    for (int tb = 0; tb < TB; ++tb)
+        route_weights<NMP>(epilogue_params<MODE>(p), tok0 + 16 * tb + r, s == 0 && tok0 + 16 * tb + r < p.T, rw[tb]);
 
     const int n_panels = (p.NC + NWK * CPW - 1) / (NWK * CPW);
     auto load_chunk = [&](chunk_t &ck, int g) __attribute__((always_inline)) {
@@ -487,7 +499,7 @@ void stream_panel_kernel(StreamParams p)
                         acc[st][tb] += lds[(((c * (NWK - 1) + w - 1) * SETS + st) * TB + tb) * kWave + lane];
         }
     }
-    if (s == 0 && jb < p.NB) epilogue<Tr, NMP, TB, MODE>(p, acc, jb, tok0, r, q);
+    if (s == 0 && jb < p.NB) epilogue<Tr, NMP, TB, MODE>(p, acc, rw, jb, tok0, r, q);
 }
 
 // ---- host side --------------------------------------------------------------------------------
