@@ -321,7 +321,7 @@ def run_widened(torch, synth, only):
             w.enable_routing(2)
             ms, wall_ms = time_steps(torch, w.routed_step, steps, warmup)
             rec = summarize(w, ms, wall_ms, "hbm")
-            rec["note"] = "same bytes as the unrouted layer; route weights applied in the epilogue"
+            rec["note"] = "same bytes as the unrouted layer; sums of the unselected masks are skipped"
         else:
             w.enable_ffn()
             ms, wall_ms = time_steps(torch, w.ffn_step, steps, warmup)

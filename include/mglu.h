@@ -155,8 +155,10 @@ typedef struct {
     /* Per-token route weights G(x)_i of the Top-K routed layer (appendix "Top-K Routing"):
      *   out = sum_i G(x)_i g(x (M_i*W)) * x ((1-M_i)*W).
      * dev, fp32 [tokens][n_masks], e.g. from mglu_route_topk; NULL means every weight is 1.
-     * Every mask's term is computed and then weighted (a weight of 0 drops it): all the masks'
-     * bits stream from memory whatever the selection, so skipping terms would save no traffic. */
+     * With at most 16 tokens (x resident in LDS) a mask whose weight is 0 for every token of the
+     * call gets no sum at all -- no operand preparation, no MFMA; the selected masks share the
+     * accumulators in compact order.  With more tokens every term is computed and then weighted.
+     * The masks' bits stream from memory whatever the selection, so the saving is arithmetic only. */
     const float *route_weights_dev;
 } mglu_variant;
 

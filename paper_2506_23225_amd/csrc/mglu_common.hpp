@@ -96,6 +96,20 @@ struct Bf16Traits {
         return r;
     }
 
+    // The same with the mask index known only at run time (uniform over the wavefront): the word
+    // that holds the bit does not depend on i, only the shift does.
+    template <int NMP>
+    __device__ static __forceinline__ frag flip_at(frag w, const uint32_t (&m)[NMP], int t, int i)
+    {
+        frag r;
+#pragma unroll
+        for (int p = 0; p < 4; ++p) {
+            const int lin0 = (4 * t + p) * NMP;
+            r[p] = w[p] ^ ((m[lin0 >> 4] << (15 - (lin0 & 15) - i)) & 0x80008000u);
+        }
+        return r;
+    }
+
     __device__ static __forceinline__ void store4(void *out, long idx, f32x4 v)
     {
         u32x2 pk;
@@ -131,6 +145,18 @@ struct F32Traits {
         for (int e = 0; e < 4; ++e) {
             const int lin = (4 * t + e) * NMP + i;
             r[e] = __uint_as_float(__float_as_uint(w[e]) ^ ((m[lin >> 5] << (31 - (lin & 31))) & 0x80000000u));
+        }
+        return r;
+    }
+
+    template <int NMP>
+    __device__ static __forceinline__ frag flip_at(frag w, const uint32_t (&m)[NMP], int t, int i)
+    {
+        frag r;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const int lin0 = (4 * t + e) * NMP;
+            r[e] = __uint_as_float(__float_as_uint(w[e]) ^ ((m[lin0 >> 5] << (31 - (lin0 & 31) - i)) & 0x80000000u));
         }
         return r;
     }

@@ -249,19 +249,59 @@ __global__ __launch_bounds__(MGLU_STREAM_MAX_WAVES *kWave) void stream_resident_
     f32x4 acc[SETS][1];
 #pragma unroll
     for (int s = 0; s < SETS; ++s) acc[s][0] = f32x4{0.f, 0.f, 0.f, 0.f};
+    // Routed layer (appendix "Top-K Routing"): a mask that no token of this block selected needs no
+    // sum at all.  The selected masks idx[0 .. n_act) take the accumulator sets 1 .. n_act, and the
+    // route weights follow them; everything here is uniform over the workgroup.
     float rw[1][NMP];
-    route_weights<NMP>(epilogue_params<MODE>(p), tok0 + r, wave == 0 && r < tc, rw[0]);
+    int n_act = p.n_masks;
+    int idx[NMP];
+#pragma unroll
+    for (int i = 0; i < NMP; ++i) idx[i] = i;
+    if constexpr (MODE == kModeMgluVariant) {
+        float w_all[NMP];
+        route_weights<NMP>(epilogue_params<MODE>(p), tok0 + r, r < tc, w_all);
+        uint32_t active = 0u;
+#pragma unroll
+        for (int i = 0; i < NMP; ++i)
+            if (i < p.n_masks && __builtin_amdgcn_ballot_w64(r < tc && w_all[i] != 0.0f) != 0) active |= 1u << i;
+        n_act = __builtin_popcount(active);
+#pragma unroll
+        for (int a = 0; a < NMP; ++a) {
+            idx[a] = active ? __builtin_ctz(active) : 0;
+            active &= active - 1;
+            rw[0][a] = w_all[0];
+#pragma unroll
+            for (int i = 1; i < NMP; ++i) rw[0][a] = idx[a] == i ? w_all[i] : rw[0][a];
+        }
+        p.n_masks = n_act;  // what the epilogue sums over
+    } else {
+        route_weights<NMP>(epilogue_params<MODE>(p), tok0 + r, false, rw[0]);
+    }
 
     auto load_chunk = [&](chunk_t &c, int kc) __attribute__((always_inline)) {
         load_wchunk<Tr, NMP, MODE>(c, wbase + (long)kc * CHUNK_BYTES, w2base + (long)kc * CHUNK_BYTES,
                                    mbase + (long)kc * kWave * NMP);
     };
     auto compute = [&](const chunk_t &c, int kc) __attribute__((always_inline)) {
+        if constexpr (MODE == kModeMgluVariant) {
 #pragma unroll
-        for (int t = 0; t < Tr::TILES; ++t) {
-            frag xf[1] = {frag{0, 0, 0, 0}};
-            if (r < tc) xf[0] = lds_x[((((kc * Tr::TILES + t) * 4 + q)) << tsh) + r];
-            mma_tile<Tr, NMP, 1, MODE>(acc, c, t, xf);
+            for (int t = 0; t < Tr::TILES; ++t) {
+                frag xf = frag{0, 0, 0, 0};
+                if (r < tc) xf = lds_x[((((kc * Tr::TILES + t) * 4 + q)) << tsh) + r];
+                acc[0][0] = Tr::mma(c.w[t], xf, acc[0][0]);
+#pragma unroll
+                for (int a = 0; a < NMP; ++a) {
+                    if (a >= n_act) break;  // uniform
+                    acc[1 + a][0] = Tr::mma(Tr::template flip_at<NMP>(c.w[t], c.m, t, idx[a]), xf, acc[1 + a][0]);
+                }
+            }
+        } else {
+#pragma unroll
+            for (int t = 0; t < Tr::TILES; ++t) {
+                frag xf[1] = {frag{0, 0, 0, 0}};
+                if (r < tc) xf[0] = lds_x[((((kc * Tr::TILES + t) * 4 + q)) << tsh) + r];
+                mma_tile<Tr, NMP, 1, MODE>(acc, c, t, xf);
+            }
         }
     };
 

@@ -89,6 +89,29 @@ def test_routed_layer_with_inactive_masks(T):
     assert torch.equal(api.mglu_forward_variant(desc, x, Wp, Mp, route_weights=ones), api.mglu_forward(desc, x, Wp, Mp))
 
 
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_routed_layer_hand_made_weights(dtype):
+    """Weights written by hand: one mask only, masks that differ from token to token, a token with no
+    mask at all (its output is exactly 0), and no mask for any token (the whole output is exactly 0)."""
+    h, d, n_m, T = 640, 112, 8, 3
+    x, W, masks = synth.make_inputs(h, d, n_m, T, dtype=dtype, seed=77, device=DEV)
+    desc, Wp, Mp = _packed(x, W, masks)
+    w = torch.zeros(T, n_m, dtype=torch.float32, device=DEV)
+    w[0, 5] = 1.0
+    w[1, 0], w[1, 7] = 0.25, 0.75
+    out = api.mglu_forward_variant(desc, x, Wp, Mp, route_weights=w)
+    ref = oracle.mglu_forward_variant(to_np64(x), to_np64(W), masks.cpu().numpy(), route=to_np64(w))
+    assert rel_err(to_np64(out), ref) <= TOL[x.dtype]
+    assert torch.count_nonzero(out[2]) == 0
+    out0 = api.mglu_forward_variant(desc, x, Wp, Mp, route_weights=torch.zeros_like(w))
+    assert torch.count_nonzero(out0) == 0
+    # one token, one mask: the n_m = 1 layer of that mask
+    d1 = api.make_desc(1, h, d, 1, x.dtype)
+    single = api.mglu_forward(d1, x[:1].contiguous(), Wp, api.mglu_pack_masks(d1, masks[5:6].contiguous()))
+    assert torch.equal(api.mglu_forward_variant(api.make_desc(1, h, d, n_m, x.dtype), x[:1].contiguous(), Wp, Mp,
+                                                route_weights=w[:1].contiguous()), single)
+
+
 @pytest.mark.parametrize("dtype,T", [("bf16", 1), ("bf16", 32), ("bf16", 200), ("f32", 3)])
 def test_linear_projection(dtype, T):
     K, N = 656, 272
