@@ -199,7 +199,7 @@ def main():
         "wall_ms_per_step": wall_ms,
         "roofline": {"bound": "hbm", "achieved": rec["GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": rec["hbm_frac"], "traffic": measured_traffic("decode_gemv"),
-                     "kernel": "mglu::stream_kernel<mglu::Bf16Traits, 4, 1, 0, true, 1>",
+                     "kernel": "mglu::stream_resident_kernel<mglu::Bf16Traits, 4, 0, 2>",
                      "bytes_per_launch": head.bytes},
     }
     if not args.no_refs:
@@ -212,6 +212,17 @@ def main():
         sink = torch.zeros(256, dtype=torch.int32, device="cuda:0")
         read_ms, _ = time_steps(torch, lambda i: api.mglu_stream_read(buf, sink), 50, 5)
         del buf
+        # the same number of bytes as one headline step, read cold by the plain read kernel: what a
+        # launch that only streams them costs on this GPU (start-up and drain included)
+        n_small = head.bytes // 16 * 16
+        smalls = [torch.empty(n_small, dtype=torch.uint8, device="cuda:0").random_(0, 255)
+                  for _ in range(max(2, int(2 * LLC_BYTES // n_small) + 1))]
+        small_ms, _ = time_steps(torch, lambda i: api.mglu_stream_read(smalls[i % len(smalls)], sink),
+                                 args.steps, args.warmup)
+        del smalls
+        result["plain_read_same_bytes"] = {"ms": small_ms, "GBps": n_small / small_ms / 1e6,
+                                           "note": "events around back-to-back launches; at this size the "
+                                                   "host's launch rate and the kernel time are about equal"}
         result["warm_cache"] = {"ms": warm_ms, "GBps": head.bytes / warm_ms / 1e6}
         result["swiglu_reference"] = {"ms": sw_ms, "GBps": head.glu_bytes / sw_ms / 1e6,
                                       "mglu_over_swiglu_time": ms / sw_ms,
