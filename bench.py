@@ -259,7 +259,10 @@ def extra_cases(synth):
         for T in (1, 32):
             cases.append(("large 8192x28672 n_m=%d T=%d" % (n_m, T),
                           synth.config("large", n_masks=n_m, tokens=T), "hbm", 60, 6))
+    # the paper's own precision on the shape of its kernel timings (4096 x 14336, 4 masks, batch 1), and its prefill twin
+    cases.append(("fp16 4096x14336 n_m=4 T=1", synth.config("prefill_8b", tokens=1, dtype="f16"), "hbm", 200, 20))
     cases.append(("prefill_8b 4096x14336 n_m=4 T=4096", synth.config("prefill_8b"), "mfma", 10, 2))
+    cases.append(("fp16 4096x14336 n_m=4 T=4096", synth.config("prefill_8b", dtype="f16"), "mfma", 10, 2))
     for n_m in (1, 2, 4, 8):
         cases.append(("large 8192x28672 n_m=%d T=2048" % n_m,
                       synth.config("large", n_masks=n_m, tokens=2048), "mfma", 5, 1))

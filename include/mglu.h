@@ -52,7 +52,11 @@ typedef enum {
 } mglu_status;
 
 /* Element type of x, W and out.  Accumulation is always fp32. */
-typedef enum { MGLU_F32 = 0, MGLU_BF16 = 1 } mglu_dtype;
+typedef enum {
+    MGLU_F32 = 0,
+    MGLU_BF16 = 1,
+    MGLU_F16 = 2   /* IEEE binary16, the precision of the paper's own kernels */
+} mglu_dtype;
 
 /* How the caller's UNPACKED weight matrix and mask planes are laid out (row-major):
  *   MGLU_W_KN: W [d_model][d_ff],  masks [n_masks][d_model][d_ff]   (the paper's math, W in R^{h x d})

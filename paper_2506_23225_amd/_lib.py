@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.environ.get("MGLU_LIBRARY_PATH") or os.path.join(HERE, "libmglu.so")
 
 MGLU_OK = 0
-MGLU_F32, MGLU_BF16 = 0, 1
+MGLU_F32, MGLU_BF16, MGLU_F16 = 0, 1, 2
 MGLU_W_KN, MGLU_W_NK = 0, 1
 
 

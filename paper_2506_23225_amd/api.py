@@ -11,7 +11,7 @@ import torch
 from . import _lib
 from ._lib import MgluDesc
 
-_DTYPE = {torch.float32: _lib.MGLU_F32, torch.bfloat16: _lib.MGLU_BF16}
+_DTYPE = {torch.float32: _lib.MGLU_F32, torch.bfloat16: _lib.MGLU_BF16, torch.float16: _lib.MGLU_F16}
 _LAYOUT = {"kn": _lib.MGLU_W_KN, "nk": _lib.MGLU_W_NK}
 
 

@@ -7,7 +7,7 @@ Compute: one dense contraction for the unmasked sum plus one per mask, the
 value branches coming from the complement for free.
 """
 
-WEIGHT_BITS = {"bf16": 16, "f32": 32}
+WEIGHT_BITS = {"bf16": 16, "f32": 32, "f16": 16}
 
 
 def mglu_weight_bits(d_model, d_ff, n_masks, dtype="bf16"):

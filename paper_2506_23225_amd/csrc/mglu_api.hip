@@ -20,6 +20,13 @@ mglu_status fail(mglu_status code, const char *fmt, ...)
     return code;
 }
 
+// the kernels' element kind of a descriptor's dtype (the two enums have the same values; spelled out
+// so that neither header depends on the other)
+int elem_of(const mglu_desc *d)
+{
+    return d->dtype == MGLU_F32 ? mglu::kElemF32 : d->dtype == MGLU_F16 ? mglu::kElemF16 : mglu::kElemBf16;
+}
+
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
@@ -28,8 +35,8 @@ size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 mglu_status check_shape(const mglu_desc *d, bool need_masks)
 {
     if (!d) return fail(MGLU_ERR_INVALID_ARG, "descriptor is NULL");
-    if (d->dtype != MGLU_F32 && d->dtype != MGLU_BF16)
-        return fail(MGLU_ERR_INVALID_ARG, "dtype %d is neither MGLU_F32 nor MGLU_BF16", (int)d->dtype);
+    if (d->dtype != MGLU_F32 && d->dtype != MGLU_BF16 && d->dtype != MGLU_F16)
+        return fail(MGLU_ERR_INVALID_ARG, "dtype %d is none of MGLU_F32, MGLU_BF16, MGLU_F16", (int)d->dtype);
     if (d->w_layout != MGLU_W_KN && d->w_layout != MGLU_W_NK)
         return fail(MGLU_ERR_INVALID_ARG, "w_layout %d is neither MGLU_W_KN nor MGLU_W_NK", (int)d->w_layout);
     if (d->d_model < 1 || d->d_ff < 1)
@@ -146,7 +153,7 @@ mglu_status mglu_pack_weights(const mglu_desc *desc, const void *W_dev, void *pa
     MGLU_TRY(check_shape(desc, false));
     MGLU_TRY(check_ptr(W_dev, "W_dev"));
     MGLU_TRY(check_ptr(packed_dev, "packed_dev"));
-    return hip_result(mglu::launch_pack_weights(pack_params(desc, W_dev, packed_dev), desc->dtype == MGLU_F32,
+    return hip_result(mglu::launch_pack_weights(pack_params(desc, W_dev, packed_dev), elem_of(desc),
                                                 static_cast<hipStream_t>(stream)),
                       "mglu_pack_weights launch");
 }
@@ -156,7 +163,7 @@ mglu_status mglu_pack_masks(const mglu_desc *desc, const uint8_t *masks_dev, voi
     MGLU_TRY(check_shape(desc, true));
     MGLU_TRY(check_ptr(masks_dev, "masks_dev"));
     MGLU_TRY(check_ptr(packed_dev, "packed_dev"));
-    return hip_result(mglu::launch_pack_masks(pack_params(desc, masks_dev, packed_dev), desc->dtype == MGLU_F32,
+    return hip_result(mglu::launch_pack_masks(pack_params(desc, masks_dev, packed_dev), elem_of(desc),
                                               static_cast<hipStream_t>(stream)),
                       "mglu_pack_masks launch");
 }
@@ -193,7 +200,7 @@ mglu_status mglu_forward_variant(const mglu_desc *desc, const mglu_variant *vari
     }
     // the main form (Swish, both branches masked, no route weights) runs the kernels without the run-time choices
     const int mode = (gate_fn != 0 || mask_use != 0 || route) ? mglu::kModeMgluVariant : mglu::kModeMglu;
-    if (desc->dtype == MGLU_BF16 && desc->tokens > kStreamMaxTokens) {
+    if (desc->dtype != MGLU_F32 && desc->tokens > kStreamMaxTokens) {
         mglu::PrefillParams pp = prefill_params(desc);
         pp.x = x_dev;
         pp.w = W_packed_dev;
@@ -202,7 +209,7 @@ mglu_status mglu_forward_variant(const mglu_desc *desc, const mglu_variant *vari
         pp.gate_fn = gate_fn;
         pp.mask_use = mask_use;
         pp.route = route;
-        return hip_result(mglu::launch_prefill(pp, mode, static_cast<hipStream_t>(stream)),
+        return hip_result(mglu::launch_prefill(pp, elem_of(desc), mode, static_cast<hipStream_t>(stream)),
                           "mglu_forward (prefill) launch");
     }
     mglu::StreamParams p = stream_params(desc);
@@ -213,7 +220,7 @@ mglu_status mglu_forward_variant(const mglu_desc *desc, const mglu_variant *vari
     p.gate_fn = gate_fn;
     p.mask_use = mask_use;
     p.route = route;
-    return hip_result(mglu::launch_stream(p, desc->dtype == MGLU_F32, mode, static_cast<hipStream_t>(stream)),
+    return hip_result(mglu::launch_stream(p, elem_of(desc), mode, static_cast<hipStream_t>(stream)),
                       "mglu_forward launch");
 }
 
@@ -229,8 +236,8 @@ mglu_status mglu_route_topk(const mglu_desc *desc, const void *x_dev, const void
                             float *weights_dev, void *stream)
 {
     if (!desc) return fail(MGLU_ERR_INVALID_ARG, "descriptor is NULL");
-    if (desc->dtype != MGLU_F32 && desc->dtype != MGLU_BF16)
-        return fail(MGLU_ERR_INVALID_ARG, "dtype %d is neither MGLU_F32 nor MGLU_BF16", (int)desc->dtype);
+    if (desc->dtype != MGLU_F32 && desc->dtype != MGLU_BF16 && desc->dtype != MGLU_F16)
+        return fail(MGLU_ERR_INVALID_ARG, "dtype %d is none of MGLU_F32, MGLU_BF16, MGLU_F16", (int)desc->dtype);
     if (desc->tokens < 1 || desc->d_model < 1)
         return fail(MGLU_ERR_INVALID_ARG, "tokens=%d and d_model=%d must be >= 1", desc->tokens, desc->d_model);
     if (desc->n_masks < 1) return fail(MGLU_ERR_INVALID_ARG, "n_masks=%d must be >= 1", desc->n_masks);
@@ -247,7 +254,7 @@ mglu_status mglu_route_topk(const mglu_desc *desc, const void *x_dev, const void
     rp.h = desc->d_model;
     rp.n_masks = desc->n_masks;
     rp.k = k;
-    return hip_result(mglu::launch_route_topk(rp, desc->dtype == MGLU_F32, static_cast<hipStream_t>(stream)),
+    return hip_result(mglu::launch_route_topk(rp, elem_of(desc), static_cast<hipStream_t>(stream)),
                       "mglu_route_topk launch");
 }
 
@@ -260,19 +267,19 @@ mglu_status mglu_linear_forward(const mglu_desc *desc, const void *a_dev, const 
     MGLU_TRY(check_ptr(out_dev, "out_dev"));
     (void)workspace_dev;
     (void)workspace_bytes;
-    if (desc->dtype == MGLU_BF16 && desc->tokens > kStreamMaxTokens) {
+    if (desc->dtype != MGLU_F32 && desc->tokens > kStreamMaxTokens) {
         mglu::PrefillParams pp = prefill_params(desc);
         pp.x = a_dev;
         pp.w = W_packed_dev;
         pp.out = out_dev;
-        return hip_result(mglu::launch_prefill(pp, mglu::kModeLinear, static_cast<hipStream_t>(stream)),
+        return hip_result(mglu::launch_prefill(pp, elem_of(desc), mglu::kModeLinear, static_cast<hipStream_t>(stream)),
                           "mglu_linear_forward (prefill) launch");
     }
     mglu::StreamParams p = stream_params(desc);
     p.x = a_dev;
     p.w = W_packed_dev;
     p.out = out_dev;
-    return hip_result(mglu::launch_stream(p, desc->dtype == MGLU_F32, mglu::kModeLinear, static_cast<hipStream_t>(stream)),
+    return hip_result(mglu::launch_stream(p, elem_of(desc), mglu::kModeLinear, static_cast<hipStream_t>(stream)),
                       "mglu_linear_forward launch");
 }
 
@@ -339,7 +346,7 @@ mglu_status mglu_projections(const mglu_desc *desc, const void *x_dev, const voi
     p.proj_t = t_dev;
     p.proj_gate = gate_dev;
     p.proj_value = value_dev;
-    return hip_result(mglu::launch_stream(p, desc->dtype == MGLU_F32, mglu::kModeProjections,
+    return hip_result(mglu::launch_stream(p, elem_of(desc), mglu::kModeProjections,
                                           static_cast<hipStream_t>(stream)),
                       "mglu_projections launch");
 }
@@ -355,13 +362,13 @@ mglu_status swiglu_forward(const mglu_desc *desc, const void *x_dev, const void 
     MGLU_TRY(check_ptr(out_dev, "out_dev"));
     (void)workspace_dev;
     (void)workspace_bytes;
-    if (desc->dtype == MGLU_BF16 && desc->tokens > kStreamMaxTokens) {
+    if (desc->dtype != MGLU_F32 && desc->tokens > kStreamMaxTokens) {
         mglu::PrefillParams pp = prefill_params(desc);
         pp.x = x_dev;
         pp.w = Wg_packed_dev;
         pp.w2 = Wv_packed_dev;
         pp.out = out_dev;
-        return hip_result(mglu::launch_prefill(pp, mglu::kModeSwiglu, static_cast<hipStream_t>(stream)),
+        return hip_result(mglu::launch_prefill(pp, elem_of(desc), mglu::kModeSwiglu, static_cast<hipStream_t>(stream)),
                           "swiglu_forward (prefill) launch");
     }
     mglu::StreamParams p = stream_params(desc);
@@ -369,7 +376,7 @@ mglu_status swiglu_forward(const mglu_desc *desc, const void *x_dev, const void 
     p.w = Wg_packed_dev;
     p.w2 = Wv_packed_dev;
     p.out = out_dev;
-    return hip_result(mglu::launch_stream(p, desc->dtype == MGLU_F32, mglu::kModeSwiglu, static_cast<hipStream_t>(stream)),
+    return hip_result(mglu::launch_stream(p, elem_of(desc), mglu::kModeSwiglu, static_cast<hipStream_t>(stream)),
                       "swiglu_forward launch");
 }
 

@@ -39,6 +39,10 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+
+// element types of x, W and out
+enum Elem { kElemF32 = 0, kElemBf16 = 1, kElemF16 = 2 };
 
 __host__ __device__ constexpr int round_up_masks(int n) { return n <= 1 ? 1 : n <= 2 ? 2 : n <= 4 ? 4 : 8; }
 __host__ __device__ constexpr long ceil_div(long a, long b) { return (a + b - 1) / b; }
@@ -61,6 +65,10 @@ __device__ __forceinline__ uint32_t f32_to_bf16_bits(float f)
     return u >> 16;
 }
 
+// fp16 (IEEE binary16), the paper's own precision: hardware conversions, round to nearest even
+__device__ __forceinline__ float f16_bits_to_f32(uint32_t b) { return (float)__builtin_bit_cast(_Float16, (uint16_t)b); }
+__device__ __forceinline__ uint32_t f32_to_f16_bits(float f) { return __builtin_bit_cast(uint16_t, (_Float16)f); }
+
 // ---- Swish, beta = 1:  z * sigmoid(z) = z / (1 + exp(-z)) --------------------------------
 __device__ __forceinline__ float swish(float z)
 {
@@ -70,18 +78,14 @@ __device__ __forceinline__ float swish(float z)
 
 // ---- element traits ------------------------------------------------------------------------
 // A chunk is TILES fragments per lane; a fragment is 16 bytes of W (A operand) or x (B operand).
-struct Bf16Traits {
-    typedef u32x4 frag;                       // 4 registers, each a (k, k+1) pair of bf16
+// 16-bit elements, two to a register.  bf16 and fp16 share the fragment shapes and -- the sign bit
+// being bit 15 of either format -- the mask application; they differ in the MFMA and the rounding.
+struct Half16Common {
+    typedef u32x4 frag;                       // 4 registers, each a (k, k+1) pair of elements
     static constexpr int TILES = 4;           // 32 k per tile
     static constexpr int TILE_K = 32;
     static constexpr int LANE_K = 8;          // consecutive k one lane holds per tile
     static constexpr int ELEM_BYTES = 2;
-
-    __device__ static __forceinline__ f32x4 mma(frag a, frag b, f32x4 c)
-    {
-        return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a),
-                                                       __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
-    }
 
     // W fragment of tile t with the sign of every element whose bit in mask i is set flipped.
     template <int NMP>
@@ -109,17 +113,47 @@ struct Bf16Traits {
         }
         return r;
     }
+};
 
+struct Bf16Traits : Half16Common {
+    __device__ static __forceinline__ f32x4 mma(frag a, frag b, f32x4 c)
+    {
+        return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a),
+                                                       __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+    }
+    __device__ static __forceinline__ uint32_t to_bits(float f) { return f32_to_bf16_bits(f); }
+    __device__ static __forceinline__ float from_bits(uint32_t b) { return bf16_bits_to_f32(b); }
     __device__ static __forceinline__ void store4(void *out, long idx, f32x4 v)
     {
         u32x2 pk;
-        pk.x = f32_to_bf16_bits(v.x) | (f32_to_bf16_bits(v.y) << 16);
-        pk.y = f32_to_bf16_bits(v.z) | (f32_to_bf16_bits(v.w) << 16);
+        pk.x = to_bits(v.x) | (to_bits(v.y) << 16);
+        pk.y = to_bits(v.z) | (to_bits(v.w) << 16);
         *reinterpret_cast<u32x2 *>(static_cast<uint16_t *>(out) + idx) = pk;
     }
     __device__ static __forceinline__ void store1(void *out, long idx, float v)
     {
-        static_cast<uint16_t *>(out)[idx] = (uint16_t)f32_to_bf16_bits(v);
+        static_cast<uint16_t *>(out)[idx] = (uint16_t)to_bits(v);
+    }
+};
+
+struct F16Traits : Half16Common {
+    __device__ static __forceinline__ f32x4 mma(frag a, frag b, f32x4 c)
+    {
+        return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b),
+                                                      c, 0, 0, 0);
+    }
+    __device__ static __forceinline__ uint32_t to_bits(float f) { return f32_to_f16_bits(f); }
+    __device__ static __forceinline__ float from_bits(uint32_t b) { return f16_bits_to_f32(b); }
+    __device__ static __forceinline__ void store4(void *out, long idx, f32x4 v)
+    {
+        u32x2 pk;
+        pk.x = to_bits(v.x) | (to_bits(v.y) << 16);
+        pk.y = to_bits(v.z) | (to_bits(v.w) << 16);
+        *reinterpret_cast<u32x2 *>(static_cast<uint16_t *>(out) + idx) = pk;
+    }
+    __device__ static __forceinline__ void store1(void *out, long idx, float v)
+    {
+        static_cast<uint16_t *>(out)[idx] = (uint16_t)to_bits(v);
     }
 };
 

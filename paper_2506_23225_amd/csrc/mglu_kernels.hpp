@@ -52,15 +52,16 @@ struct PackParams {
     int nk;               // 0: [h][d] (masks [n][h][d]); 1: [d][h] (masks [n][d][h])
 };
 
-hipError_t launch_stream(const StreamParams &p, bool is_f32, int mode, hipStream_t stream);
-int stream_max_token_blocks(int nmp, bool is_f32);
+// `elem` is an Elem (mglu_common.hpp): the element type of x, W and out
+hipError_t launch_stream(const StreamParams &p, int elem, int mode, hipStream_t stream);
+int stream_max_token_blocks(int nmp, int elem);
 hipError_t launch_stream_read(const void *buf, size_t bytes, uint32_t *sink, hipStream_t stream);
 
-hipError_t launch_prefill(const PrefillParams &p, int mode, hipStream_t stream);
+hipError_t launch_prefill(const PrefillParams &p, int elem, int mode, hipStream_t stream);   // 16-bit elements only
 
-hipError_t launch_route_topk(const RouteParams &p, bool is_f32, hipStream_t stream);
+hipError_t launch_route_topk(const RouteParams &p, int elem, hipStream_t stream);
 
-hipError_t launch_pack_weights(const PackParams &p, bool is_f32, hipStream_t stream);
-hipError_t launch_pack_masks(const PackParams &p, bool is_f32, hipStream_t stream);
+hipError_t launch_pack_weights(const PackParams &p, int elem, hipStream_t stream);
+hipError_t launch_pack_masks(const PackParams &p, int elem, hipStream_t stream);
 
 }  // namespace mglu

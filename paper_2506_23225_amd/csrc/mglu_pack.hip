@@ -95,8 +95,9 @@ __global__ __launch_bounds__(256) void pack_masks_kernel(PackParams p)
     }
 }
 
-hipError_t launch_pack_weights(const PackParams &p, bool is_f32, hipStream_t stream)
+hipError_t launch_pack_weights(const PackParams &p, int elem, hipStream_t stream)
 {
+    const bool is_f32 = elem == kElemF32;   // bf16 and fp16 are both moved as 16-bit words
     const int tiles = is_f32 ? F32Traits::TILES : Bf16Traits::TILES;
     const long total = (long)p.NB * p.NC * tiles * kWave;
     const unsigned blocks = (unsigned)ceil_div(total, 256);
@@ -121,8 +122,9 @@ static hipError_t launch_pack_masks_t(const PackParams &p, hipStream_t stream)
     return hipGetLastError();
 }
 
-hipError_t launch_pack_masks(const PackParams &p, bool is_f32, hipStream_t stream)
+hipError_t launch_pack_masks(const PackParams &p, int elem, hipStream_t stream)
 {
+    const bool is_f32 = elem == kElemF32;   // the mask words of bf16 and fp16 are laid out alike
     return is_f32 ? launch_pack_masks_t<F32Traits>(p, stream) : launch_pack_masks_t<Bf16Traits>(p, stream);
 }
 

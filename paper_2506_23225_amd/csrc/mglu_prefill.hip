@@ -47,12 +47,11 @@ namespace mglu {
 constexpr int kPrefillWaves = MGLU_PREFILL_WAVES;
 
 // AD: how many tiles ahead of the multiply the A fragments are fetched.
-template <int NMP, int CB, int TB, int MODE, int AD>
+template <typename Tr, int NMP, int CB, int TB, int MODE, int AD>
 __global__ __launch_bounds__(kPrefillWaves *kWave) __attribute__((amdgpu_waves_per_eu(2, 2)))
 void prefill_kernel(PrefillParams p)
 {
-    typedef Bf16Traits Tr;
-    typedef Tr::frag frag;
+    typedef typename Tr::frag frag;
     constexpr int SETS = sets_of(MODE, NMP);
     constexpr int AR = 4;                       // ring entries (one per tile of a chunk)
     constexpr long CHUNK_BYTES = (long)kColBlock * kChunkK * 2;
@@ -312,7 +311,7 @@ void prefill_kernel(PrefillParams p)
 
 // ---- host side --------------------------------------------------------------------------------
 
-template <int NMP, int CB, int TB, int MODE, int AD>
+template <typename Tr, int NMP, int CB, int TB, int MODE, int AD>
 static hipError_t launch_prefill_one(PrefillParams p, hipStream_t stream)
 {
     const int bm = 16 * TB, bn = kPrefillWaves * kColBlock * CB;
@@ -323,29 +322,35 @@ static hipError_t launch_prefill_one(PrefillParams p, hipStream_t stream)
     const int per_xcd = (p.tiles_n + 7) / 8;
     const long wgs = (long)8 * per_xcd * p.tiles_m;
     const size_t lds = (size_t)2 * 4 * TB * kWave * sizeof(f32x4);
-    auto kern = prefill_kernel<NMP, CB, TB, MODE, AD>;
+    auto kern = prefill_kernel<Tr, NMP, CB, TB, MODE, AD>;
     hipLaunchKernelGGL(kern, dim3((unsigned)wgs), dim3(kPrefillWaves * kWave), lds, stream, p);
     return hipGetLastError();
 }
 
-hipError_t launch_prefill(const PrefillParams &p, int mode, hipStream_t stream)
+template <typename Tr>
+static hipError_t launch_prefill_t(const PrefillParams &p, int mode, hipStream_t stream)
 {
-    if (mode == kModeSwiglu) return launch_prefill_one<1, 2, 8, kModeSwiglu, 1>(p, stream);
-    if (mode == kModeLinear) return launch_prefill_one<1, 2, 8, kModeLinear, 2>(p, stream);
+    if (mode == kModeSwiglu) return launch_prefill_one<Tr, 1, 2, 8, kModeSwiglu, 1>(p, stream);
+    if (mode == kModeLinear) return launch_prefill_one<Tr, 1, 2, 8, kModeLinear, 2>(p, stream);
     if (mode == kModeMgluVariant) {
         switch (round_up_masks(p.n_masks)) {
-        case 1: return launch_prefill_one<1, 2, 8, kModeMgluVariant, 1>(p, stream);
-        case 2: return launch_prefill_one<2, 1, 8, kModeMgluVariant, 2>(p, stream);
-        case 4: return launch_prefill_one<4, 1, MGLU_PREFILL_TB4, kModeMgluVariant, MGLU_PREFILL_AD4>(p, stream);
-        default: return launch_prefill_one<8, 1, 4, kModeMgluVariant, 2>(p, stream);
+        case 1: return launch_prefill_one<Tr, 1, 2, 8, kModeMgluVariant, 1>(p, stream);
+        case 2: return launch_prefill_one<Tr, 2, 1, 8, kModeMgluVariant, 2>(p, stream);
+        case 4: return launch_prefill_one<Tr, 4, 1, MGLU_PREFILL_TB4, kModeMgluVariant, MGLU_PREFILL_AD4>(p, stream);
+        default: return launch_prefill_one<Tr, 8, 1, 4, kModeMgluVariant, 2>(p, stream);
         }
     }
     switch (round_up_masks(p.n_masks)) {
-    case 1: return launch_prefill_one<1, 2, 8, kModeMglu, 1>(p, stream);
-    case 2: return launch_prefill_one<2, 1, 8, kModeMglu, 2>(p, stream);
-    case 4: return launch_prefill_one<4, 1, MGLU_PREFILL_TB4, kModeMglu, MGLU_PREFILL_AD4>(p, stream);
-    default: return launch_prefill_one<8, 1, 4, kModeMglu, 2>(p, stream);
+    case 1: return launch_prefill_one<Tr, 1, 2, 8, kModeMglu, 1>(p, stream);
+    case 2: return launch_prefill_one<Tr, 2, 1, 8, kModeMglu, 2>(p, stream);
+    case 4: return launch_prefill_one<Tr, 4, 1, MGLU_PREFILL_TB4, kModeMglu, MGLU_PREFILL_AD4>(p, stream);
+    default: return launch_prefill_one<Tr, 8, 1, 4, kModeMglu, 2>(p, stream);
     }
+}
+
+hipError_t launch_prefill(const PrefillParams &p, int elem, int mode, hipStream_t stream)
+{
+    return elem == kElemF16 ? launch_prefill_t<F16Traits>(p, mode, stream) : launch_prefill_t<Bf16Traits>(p, mode, stream);
 }
 
 }  // namespace mglu

@@ -15,6 +15,11 @@ __device__ __forceinline__ float route_elem<uint16_t>(const void *p, long i)
 {
     return bf16_bits_to_f32(static_cast<const uint16_t *>(p)[i]);
 }
+template <>
+__device__ __forceinline__ float route_elem<_Float16>(const void *p, long i)
+{
+    return (float)static_cast<const _Float16 *>(p)[i];
+}
 
 template <typename elem_t>
 __global__ __launch_bounds__(256) void route_topk_kernel(RouteParams p)
@@ -63,10 +68,11 @@ __global__ __launch_bounds__(256) void route_topk_kernel(RouteParams p)
         if (i < p.n_masks) p.weights[(long)tok * p.n_masks + i] = kept[i] ? __expf(logit[i] - top) / sum : 0.f;
 }
 
-hipError_t launch_route_topk(const RouteParams &p, bool is_f32, hipStream_t stream)
+hipError_t launch_route_topk(const RouteParams &p, int elem, hipStream_t stream)
 {
     const dim3 grid((unsigned)ceil_div(p.T, 4)), block(256);
-    if (is_f32) hipLaunchKernelGGL(route_topk_kernel<float>, grid, block, 0, stream, p);
+    if (elem == kElemF32) hipLaunchKernelGGL(route_topk_kernel<float>, grid, block, 0, stream, p);
+    else if (elem == kElemF16) hipLaunchKernelGGL(route_topk_kernel<_Float16>, grid, block, 0, stream, p);
     else hipLaunchKernelGGL(route_topk_kernel<uint16_t>, grid, block, 0, stream, p);
     return hipGetLastError();
 }

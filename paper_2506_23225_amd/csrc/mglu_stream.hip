@@ -545,7 +545,7 @@ void stream_panel_kernel(StreamParams p)
 // ---- host side --------------------------------------------------------------------------------
 
 // Largest token-block count per workgroup the 256-register budget allows in the panel kernel.
-int stream_max_token_blocks(int nmp, bool is_f32) { return is_f32 ? 1 : nmp <= 2 ? 4 : 2; }
+int stream_max_token_blocks(int nmp, int elem) { return elem == kElemF32 ? 1 : nmp <= 2 ? 4 : 2; }
 
 struct PanelWide  { static constexpr int NWC = 8, NWK = 1, CPW = 2; };
 struct PanelSplit { static constexpr int NWC = 4, NWK = 2, CPW = 1; };
@@ -560,8 +560,9 @@ struct StreamPlan {
     dim3 grid, block;
 };
 
-static StreamPlan plan_stream(const StreamParams &p, bool is_f32, int nmp, int sets)
+static StreamPlan plan_stream(const StreamParams &p, int elem_kind, int nmp, int sets)
 {
+    const bool is_f32 = elem_kind == kElemF32;
     constexpr size_t kLdsBudget = 56 * 1024;
     const int elem = is_f32 ? 4 : 2;
     const int tiles = is_f32 ? F32Traits::TILES : Bf16Traits::TILES;
@@ -585,7 +586,7 @@ static StreamPlan plan_stream(const StreamParams &p, bool is_f32, int nmp, int s
         return pl;
     }
     const int blocks = (int)ceil_div(p.T, 16);
-    const int max_tb = stream_max_token_blocks(nmp, is_f32);
+    const int max_tb = stream_max_token_blocks(nmp, elem_kind);
     pl.resident = false;
     pl.tb = (blocks >= 4 && max_tb >= 4) ? 4 : (blocks >= 2 && max_tb >= 2) ? 2 : 1;
     pl.wide = ceil_div(p.NB, PanelWide::NWC) >= MGLU_PANEL_WIDE_MIN_WGS;
@@ -656,26 +657,25 @@ static hipError_t launch_nmp(const StreamParams &p, int nmp, const StreamPlan &p
     }
 }
 
-hipError_t launch_stream(const StreamParams &p, bool is_f32, int mode, hipStream_t stream)
+template <typename Tr>
+static hipError_t launch_mode(const StreamParams &p, int mode, int nmp, const StreamPlan &pl, hipStream_t stream)
+{
+    switch (mode) {
+    case kModeMglu: return launch_nmp<Tr, kModeMglu>(p, nmp, pl, stream);
+    case kModeMgluVariant: return launch_nmp<Tr, kModeMgluVariant>(p, nmp, pl, stream);
+    case kModeProjections: return launch_nmp<Tr, kModeProjections>(p, nmp, pl, stream);
+    case kModeLinear: return launch_plan<Tr, 1, kModeLinear>(p, pl, stream);
+    default: return launch_plan<Tr, 1, kModeSwiglu>(p, pl, stream);
+    }
+}
+
+hipError_t launch_stream(const StreamParams &p, int elem, int mode, hipStream_t stream)
 {
     const int nmp = (mode == kModeSwiglu || mode == kModeLinear) ? 1 : round_up_masks(p.n_masks);
-    const StreamPlan pl = plan_stream(p, is_f32, nmp, sets_of(mode, nmp));
-    if (is_f32) {
-        switch (mode) {
-        case kModeMglu: return launch_nmp<F32Traits, kModeMglu>(p, nmp, pl, stream);
-        case kModeMgluVariant: return launch_nmp<F32Traits, kModeMgluVariant>(p, nmp, pl, stream);
-        case kModeProjections: return launch_nmp<F32Traits, kModeProjections>(p, nmp, pl, stream);
-        case kModeLinear: return launch_plan<F32Traits, 1, kModeLinear>(p, pl, stream);
-        default: return launch_plan<F32Traits, 1, kModeSwiglu>(p, pl, stream);
-        }
-    }
-    switch (mode) {
-    case kModeMglu: return launch_nmp<Bf16Traits, kModeMglu>(p, nmp, pl, stream);
-    case kModeMgluVariant: return launch_nmp<Bf16Traits, kModeMgluVariant>(p, nmp, pl, stream);
-    case kModeProjections: return launch_nmp<Bf16Traits, kModeProjections>(p, nmp, pl, stream);
-    case kModeLinear: return launch_plan<Bf16Traits, 1, kModeLinear>(p, pl, stream);
-    default: return launch_plan<Bf16Traits, 1, kModeSwiglu>(p, pl, stream);
-    }
+    const StreamPlan pl = plan_stream(p, elem, nmp, sets_of(mode, nmp));
+    if (elem == kElemF32) return launch_mode<F32Traits>(p, mode, nmp, pl, stream);
+    if (elem == kElemF16) return launch_mode<F16Traits>(p, mode, nmp, pl, stream);
+    return launch_mode<Bf16Traits>(p, mode, nmp, pl, stream);
 }
 
 // ---- read-bandwidth calibrator: the same 16-byte-per-lane, 1 KiB-per-wavefront loads, nothing else ----

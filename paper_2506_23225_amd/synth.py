@@ -25,7 +25,7 @@ CONFIGS = {
     "large":       dict(d_model=8192, d_ff=28672, n_masks=4, tokens=1,    dtype="bf16", w_std=0.01),
 }
 
-TORCH_DTYPE = {"f32": torch.float32, "bf16": torch.bfloat16}
+TORCH_DTYPE = {"f32": torch.float32, "bf16": torch.bfloat16, "f16": torch.float16}
 
 
 def config(name, **overrides):

@@ -2,8 +2,10 @@
 import numpy as np
 import torch
 
-# spec tolerances: max relative error, bf16 inputs 2e-2, fp32 inputs 1e-4
-TOL = {torch.bfloat16: 2e-2, torch.float32: 1e-4}
+# spec tolerances: max relative error, bf16 inputs 2e-2, fp32 inputs 1e-4; fp16 (not among
+# the benchmark spec's types) gets the bf16 bar scaled by the ratio of the two formats' rounding units,
+# 2^-11 / 2^-8: the final rounding to the output type dominates the error of both
+TOL = {torch.bfloat16: 2e-2, torch.float32: 1e-4, torch.float16: 2.5e-3}
 
 
 def rel_err(y, ref):

@@ -45,7 +45,7 @@ def test_tiny_fp32_config():
     print("tiny fp32 rel err", _check_full(x, W, masks, out))
 
 
-@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("dtype", ["bf16", "f32", "f16"])
 @pytest.mark.parametrize("T,h,d,n_m", [
     (1, 8, 1, 1), (1, 128, 16, 1), (3, 200, 50, 3), (16, 256, 688, 2), (17, 136, 17, 5),
     (33, 1024, 100, 8), (5, 2048, 48, 4), (2, 520, 36, 7), (64, 384, 64, 1), (70, 256, 40, 2),
@@ -75,6 +75,27 @@ def test_prefill_kernel_ragged_shapes(T, h, d, n_m):
     _check_full(x, W, masks, _run(x, W, masks))
 
 
+@pytest.mark.parametrize("T,h,d,n_m", [(40, 384, 25616, 2), (200, 520, 272, 4), (300, 384, 1000, 8), (129, 1024, 130, 1)])
+def test_fp16_panel_and_tiled_kernels(T, h, d, n_m):
+    """fp16, the paper's own precision, through the panel kernel and the MFMA-tiled kernel."""
+    x, W, masks = synth.make_inputs(h, d, n_m, T, dtype="f16", seed=T + h + d, device=DEV)
+    out = _run(x, W, masks)
+    if d > 4096:
+        _check_columns(x, W, masks, out, edge_columns(d, n_random=256, seed=T))
+    else:
+        _check_full(x, W, masks, out)
+
+
+@pytest.mark.parametrize("T", [1, 4096])
+def test_fp16_paper_shape_sampled(T):
+    """4096 x 14336 with 4 masks in fp16: the shape and precision of the paper's kernel timings."""
+    cfg = synth.config("prefill_8b", tokens=T, dtype="f16")
+    x, W, masks = synth.make_inputs(**cfg, seed=0, device=DEV)
+    out = _run(x, W, masks)
+    print("fp16 4096x14336 T=%d rel err" % T,
+          _check_columns(x, W, masks, out, edge_columns(cfg["d_ff"], n_random=48 if T > 1 else 128)))
+
+
 def test_kernel_hand_over_at_64_tokens():
     """64 tokens run on the streaming (panel) kernel, 65 on the MFMA-tiled one: both against the oracle,
     and the shared rows against each other (they may differ by summation order only)."""
@@ -97,7 +118,7 @@ def test_prefill_kernel_other_layout_and_entries():
     assert torch.equal(_run(x, W, masks * 255), ref)           # any non-zero byte means "gate"
 
 
-@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("dtype", ["bf16", "f32", "f16"])
 def test_nk_layout_and_bool_entry(dtype):
     x, W, masks = synth.make_inputs(392, 72, 3, 4, dtype=dtype, seed=5, device=DEV)
     ref = _run(x, W, masks)
@@ -157,7 +178,7 @@ def test_projections_partition_and_oracle():
         assert np.abs(to_np64(gate[i] + value[i]) - dense).max() <= 1e-5 * scale
 
 
-@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("dtype", ["bf16", "f32", "f16"])
 def test_degenerate_masks_and_inputs(dtype):
     """Cases whose exact answer is 0.  All-value masks and one-hot inputs give 0 bit for bit.
     An all-gate mask gives value_i = (t + dsum_i)/2 with dsum_i the sum of the negated terms;
@@ -177,7 +198,7 @@ def test_degenerate_masks_and_inputs(dtype):
     base = _run(x, W, masks)
     assert torch.equal(_run(x, W, torch.cat([masks, 1 - ones[:1]])), base)
     more = _run(x, W, torch.cat([masks, ones[:1]]))
-    assert rel_err(to_np64(more), to_np64(base)) <= (1e-2 if dtype == "bf16" else 1e-5)
+    assert rel_err(to_np64(more), to_np64(base)) <= {"bf16": 1e-2, "f16": 2e-3, "f32": 1e-5}[dtype]
 
 
 def test_rows_independent_and_mask_order_and_determinism():
@@ -190,7 +211,7 @@ def test_rows_independent_and_mask_order_and_determinism():
     assert rel_err(to_np64(perm), to_np64(full)) <= 1e-2       # fp32 sum order differs, value does not
 
 
-@pytest.mark.parametrize("dtype,T", [("bf16", 1), ("bf16", 16), ("f32", 3), ("bf16", 150)])
+@pytest.mark.parametrize("dtype,T", [("bf16", 1), ("bf16", 16), ("f32", 3), ("bf16", 150), ("f16", 2), ("f16", 90)])
 def test_swiglu_reference_kernel(dtype, T):
     xg, Wg, _ = synth.make_inputs(768, 208, 1, T, dtype=dtype, seed=6, device=DEV)
     _, Wv, _ = synth.make_inputs(768, 208, 1, T, dtype=dtype, seed=7, device=DEV)

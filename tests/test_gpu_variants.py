@@ -50,7 +50,7 @@ def test_variants_fp32():
     assert rel_err(to_np64(out), ref) <= TOL[x.dtype]
 
 
-@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("dtype", ["bf16", "f32", "f16"])
 @pytest.mark.parametrize("T,k", [(1, 2), (16, 1), (300, 3), (64, 8)])
 def test_router_topk(dtype, T, k):
     h, n_m = 384, 8
@@ -89,7 +89,7 @@ def test_routed_layer_with_inactive_masks(T):
     assert torch.equal(api.mglu_forward_variant(desc, x, Wp, Mp, route_weights=ones), api.mglu_forward(desc, x, Wp, Mp))
 
 
-@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("dtype", ["bf16", "f32", "f16"])
 def test_routed_layer_hand_made_weights(dtype):
     """Weights written by hand: one mask only, masks that differ from token to token, a token with no
     mask at all (its output is exactly 0), and no mask for any token (the whole output is exactly 0)."""
@@ -112,7 +112,7 @@ def test_routed_layer_hand_made_weights(dtype):
                                                 route_weights=w[:1].contiguous()), single)
 
 
-@pytest.mark.parametrize("dtype,T", [("bf16", 1), ("bf16", 32), ("bf16", 200), ("f32", 3)])
+@pytest.mark.parametrize("dtype,T", [("bf16", 1), ("bf16", 32), ("bf16", 200), ("f32", 3), ("f16", 5), ("f16", 120)])
 def test_linear_projection(dtype, T):
     K, N = 656, 272
     a, W, _ = synth.make_inputs(K, N, 1, T, dtype=dtype, seed=T, device=DEV)
