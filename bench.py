@@ -263,6 +263,9 @@ def extra_cases(synth):
     cases.append(("fp16 4096x14336 n_m=4 T=1", synth.config("prefill_8b", tokens=1, dtype="f16"), "hbm", 200, 20))
     cases.append(("prefill_8b 4096x14336 n_m=4 T=4096", synth.config("prefill_8b"), "mfma", 10, 2))
     cases.append(("fp16 4096x14336 n_m=4 T=4096", synth.config("prefill_8b", dtype="f16"), "mfma", 10, 2))
+    # 16 masks, the paper's largest ablation
+    cases.append(("decode_8b 4096x14336 n_m=16 T=1", synth.config("decode_8b", n_masks=16, tokens=1), "hbm", 100, 10))
+    cases.append(("prefill_8b 4096x14336 n_m=16 T=4096", synth.config("prefill_8b", n_masks=16), "mfma", 5, 1))
     for n_m in (1, 2, 4, 8):
         cases.append(("large 8192x28672 n_m=%d T=2048" % n_m,
                       synth.config("large", n_masks=n_m, tokens=2048), "mfma", 5, 1))

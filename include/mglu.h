@@ -46,7 +46,7 @@ extern "C" {
 typedef enum {
     MGLU_OK = 0,
     MGLU_ERR_INVALID_ARG = 1,  /* null pointer, misaligned pointer, non-positive size, bad enum */
-    MGLU_ERR_UNSUPPORTED = 2,  /* valid in principle, not built (e.g. n_masks > 8) */
+    MGLU_ERR_UNSUPPORTED = 2,  /* valid in principle, not built (e.g. n_masks > 16) */
     MGLU_ERR_WORKSPACE = 3,    /* workspace missing or smaller than the query says */
     MGLU_ERR_HIP = 4           /* the HIP runtime refused a launch */
 } mglu_status;
@@ -68,7 +68,7 @@ typedef struct {
     int32_t tokens;      /* T >= 1: rows of x and out (ignored by the pack calls) */
     int32_t d_model;     /* h >= 1: reduction length */
     int32_t d_ff;        /* d >= 1: output width */
-    int32_t n_masks;     /* n_m in [1, 8] */
+    int32_t n_masks;     /* n_m in [1, 16] */
     mglu_dtype dtype;
     mglu_layout w_layout;
 } mglu_desc;
@@ -90,7 +90,7 @@ size_t mglu_packed_weight_bytes(const mglu_desc *desc);
 mglu_status mglu_pack_weights(const mglu_desc *desc, const void *W_dev, void *packed_dev, void *stream);
 
 /* Bytes of the packed mask buffer: one bit per mask per (padded) weight element, with
- * n_masks rounded up to 1, 2, 4 or 8 (the padding planes are all-zero, i.e. all-value,
+ * n_masks rounded up to 1, 2, 4, 8 or 16 (the padding planes are all-zero, i.e. all-value,
  * and contribute exactly 0 to Eq. 3).  0 on a bad descriptor. */
 size_t mglu_packed_mask_bytes(const mglu_desc *desc);
 

@@ -43,7 +43,8 @@ mglu_status check_shape(const mglu_desc *d, bool need_masks)
         return fail(MGLU_ERR_INVALID_ARG, "d_model=%d and d_ff=%d must be >= 1", d->d_model, d->d_ff);
     if (need_masks) {
         if (d->n_masks < 1) return fail(MGLU_ERR_INVALID_ARG, "n_masks=%d must be >= 1", d->n_masks);
-        if (d->n_masks > 8) return fail(MGLU_ERR_UNSUPPORTED, "n_masks=%d: at most 8 masks are supported", d->n_masks);
+        if (d->n_masks > mglu::kMaxMasks)
+            return fail(MGLU_ERR_UNSUPPORTED, "n_masks=%d: at most %d masks are supported", d->n_masks, mglu::kMaxMasks);
     }
     const long nb = mglu::ceil_div(d->d_ff, mglu::kColBlock), nc = mglu::ceil_div(d->d_model, mglu::kChunkK);
     if (nb > 0x7fffffffL / 64 || nb * nc > 0x7fffffffL / 8)
@@ -241,7 +242,8 @@ mglu_status mglu_route_topk(const mglu_desc *desc, const void *x_dev, const void
     if (desc->tokens < 1 || desc->d_model < 1)
         return fail(MGLU_ERR_INVALID_ARG, "tokens=%d and d_model=%d must be >= 1", desc->tokens, desc->d_model);
     if (desc->n_masks < 1) return fail(MGLU_ERR_INVALID_ARG, "n_masks=%d must be >= 1", desc->n_masks);
-    if (desc->n_masks > 8) return fail(MGLU_ERR_UNSUPPORTED, "n_masks=%d: at most 8 masks are supported", desc->n_masks);
+    if (desc->n_masks > mglu::kMaxMasks)
+        return fail(MGLU_ERR_UNSUPPORTED, "n_masks=%d: at most %d masks are supported", desc->n_masks, mglu::kMaxMasks);
     if (k < 1 || k > desc->n_masks) return fail(MGLU_ERR_INVALID_ARG, "k=%d must be in [1, n_masks=%d]", k, desc->n_masks);
     MGLU_TRY(check_ptr(x_dev, "x_dev"));
     MGLU_TRY(check_ptr(Wr_dev, "Wr_dev"));

@@ -15,9 +15,9 @@
 // lane%16, eight consecutive k per lane) or, for fp32, of four
 // v_mfma_f32_16x16x4_f32 (row = lane%16, k = lane/16, one per e).
 //
-//   masks  [jb][kc][lane<64][word<NMP]  uint32,  NMP = n_masks rounded up to 1,2,4,8
-//          (NMP = 8: [jb][kc][half<2][lane<64][word<4], word w of a lane = half w/4, word w%4, so
-//           that every 16-byte-per-lane load of a wavefront is one contiguous 1 KiB run)
+//   masks  [jb][kc][lane<64][word<NMP]  uint32,  NMP = n_masks rounded up to 1,2,4,8,16
+//          (NMP >= 8: [jb][kc][piece<NMP/4][lane<64][word<4], word w of a lane = piece w/4, word w%4,
+//           so that every 16-byte-per-lane load of a wavefront is one contiguous 1 KiB run)
 //
 // A lane's NMP words hold the NMP x 32 mask bits of the 32 weight elements that
 // lane holds in the chunk.  bf16: the elements form 16 register pairs
@@ -44,14 +44,15 @@ typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 // element types of x, W and out
 enum Elem { kElemF32 = 0, kElemBf16 = 1, kElemF16 = 2 };
 
-__host__ __device__ constexpr int round_up_masks(int n) { return n <= 1 ? 1 : n <= 2 ? 2 : n <= 4 ? 4 : 8; }
+constexpr int kMaxMasks = 16;
+__host__ __device__ constexpr int round_up_masks(int n) { return n <= 1 ? 1 : n <= 2 ? 2 : n <= 4 ? 4 : n <= 8 ? 8 : 16; }
 __host__ __device__ constexpr long ceil_div(long a, long b) { return (a + b - 1) / b; }
 
-// Byte offset of a lane's mask words inside a chunk's mask block, and the stride between its two
-// 16-byte halves when there are 8 masks.
+// Byte offset of a lane's mask words inside a chunk's mask block, and the stride between its
+// 16-byte pieces when there are 8 or 16 masks.
 template <int NMP>
-__host__ __device__ constexpr uint32_t mask_lane_bytes(int lane) { return NMP == 8 ? lane * 16 : lane * NMP * 4; }
-constexpr uint32_t kMaskHalfBytes = kWave * 16;
+__host__ __device__ constexpr uint32_t mask_lane_bytes(int lane) { return NMP >= 8 ? lane * 16 : lane * NMP * 4; }
+constexpr uint32_t kMaskPieceBytes = kWave * 16;
 
 // ---- fp32 <-> bf16 ---------------------------------------------------------------------
 __device__ __forceinline__ float bf16_bits_to_f32(uint32_t b) { return __uint_as_float(b << 16); }

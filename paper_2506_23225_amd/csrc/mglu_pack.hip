@@ -82,10 +82,10 @@ __global__ __launch_bounds__(256) void pack_masks_kernel(PackParams p)
             }
         }
     }
-    // 16 bytes per lane per wavefront load: with 8 masks the lane's 8 words go to two 1 KiB halves
-    // of the chunk's mask block (words 0-3, then words 4-7), so each load is one contiguous run
-    if (NMP == 8) {
-        uint32_t *dst = static_cast<uint32_t *>(p.dst) + (gid / kWave) * (kWave * 8) + lane * 4;
+    // 16 bytes per lane per wavefront load: with 8 or 16 masks the lane's words go to NMP / 4 pieces
+    // of 1 KiB of the chunk's mask block (words 0-3, then words 4-7, ...), so each load is one contiguous run
+    if (NMP >= 8) {
+        uint32_t *dst = static_cast<uint32_t *>(p.dst) + (gid / kWave) * (kWave * NMP) + lane * 4;
 #pragma unroll
         for (int w = 0; w < NMP; ++w) dst[(w / 4) * (kWave * 4) + (w % 4)] = words[w];
     } else {
@@ -117,7 +117,8 @@ static hipError_t launch_pack_masks_t(const PackParams &p, hipStream_t stream)
     case 1: hipLaunchKernelGGL((pack_masks_kernel<Tr, 1>), grid, block, 0, stream, p); break;
     case 2: hipLaunchKernelGGL((pack_masks_kernel<Tr, 2>), grid, block, 0, stream, p); break;
     case 4: hipLaunchKernelGGL((pack_masks_kernel<Tr, 4>), grid, block, 0, stream, p); break;
-    default: hipLaunchKernelGGL((pack_masks_kernel<Tr, 8>), grid, block, 0, stream, p); break;
+    case 8: hipLaunchKernelGGL((pack_masks_kernel<Tr, 8>), grid, block, 0, stream, p); break;
+    default: hipLaunchKernelGGL((pack_masks_kernel<Tr, 16>), grid, block, 0, stream, p); break;
     }
     return hipGetLastError();
 }

@@ -153,11 +153,13 @@ void prefill_kernel(PrefillParams p)
             for (int cb = 0; cb < CB; ++cb) {
                 const uint32_t *mp =
                     reinterpret_cast<const uint32_t *>(mbase[cb] + (long)kc * (kWave * NMP * 4) + lane_m);
-                if constexpr (NMP == 8) {
-                    u32x4 a = *reinterpret_cast<const u32x4 *>(mp);
-                    u32x4 b = *reinterpret_cast<const u32x4 *>(reinterpret_cast<const char *>(mp) + kMaskHalfBytes);
+                if constexpr (NMP >= 8) {
 #pragma unroll
-                    for (int i = 0; i < 4; ++i) { mk[slot][cb][i] = a[i]; mk[slot][cb][4 + i] = b[i]; }
+                    for (int piece = 0; piece < NMP / 4; ++piece) {
+                        u32x4 a = *reinterpret_cast<const u32x4 *>(reinterpret_cast<const char *>(mp) + piece * kMaskPieceBytes);
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) mk[slot][cb][4 * piece + i] = a[i];
+                    }
                 } else if constexpr (NMP == 4) {
                     u32x4 a = *reinterpret_cast<const u32x4 *>(mp);
 #pragma unroll
@@ -222,35 +224,63 @@ void prefill_kernel(PrefillParams p)
             if (t == 0) load_masks(kn, MS ^ 1);
             __builtin_amdgcn_sched_barrier(0);
 
-            // operand variants of this tile: W itself and W with mask i's gate elements negated
-            frag var[SETS][CB];
-#pragma unroll
-            for (int cb = 0; cb < CB; ++cb) {
-                var[0][cb] = aw[t][cb];
-                if constexpr (MODE == kModeSwiglu) {
-                    var[1][cb] = aw2[t][cb];
-                } else if constexpr (MODE != kModeLinear) {
-#pragma unroll
-                    for (int i = 0; i < NMP; ++i) var[1 + i][cb] = Tr::template flip<NMP>(aw[t][cb], mk[MS][cb], t, i);
-                }
-            }
-#pragma unroll
-            for (int pi = 0; pi < PAIRS; ++pi) {
-                const bool more = (pi + 1 < PAIRS) || (t + 1 < 4);
+            if constexpr (TB == 2 && MODE != kModeSwiglu && MODE != kModeLinear) {
+                // Many masks, one pair of token blocks: each mask's operand is prepared right before its
+                // two MFMAs and dropped after them (all variants at once would not fit the registers);
+                // the issue-order groups keep the compiler from gathering the preparation up front.
+                const bool more = t + 1 < 4;
                 if (more) {
-                    read_pair(bnxt, pi + 1 < PAIRS ? t : t + 1, pi + 1 < PAIRS ? pi + 1 : 0);
+                    read_pair(bnxt, t + 1, 0);
                     asm volatile("s_waitcnt lgkmcnt(2)" : "+v"(bcur[0]), "+v"(bcur[1]));
                 } else {
                     asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(bcur[0]), "+v"(bcur[1]));
                 }
 #pragma unroll
-                for (int h2 = 0; h2 < 2; ++h2)
+                for (int cb = 0; cb < CB; ++cb) {
 #pragma unroll
-                    for (int s = 0; s < SETS; ++s)
+                    for (int h2 = 0; h2 < 2; ++h2) acc[0][cb][h2] = Tr::mma(aw[t][cb], bcur[h2], acc[0][cb][h2]);
+                    __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
 #pragma unroll
-                        for (int cb = 0; cb < CB; ++cb)
-                            acc[s][cb][2 * pi + h2] = Tr::mma(var[s][cb], bcur[h2], acc[s][cb][2 * pi + h2]);
+                    for (int i = 0; i < NMP; ++i) {
+                        const frag wf = Tr::template flip<NMP>(aw[t][cb], mk[MS][cb], t, i);
+#pragma unroll
+                        for (int h2 = 0; h2 < 2; ++h2) acc[1 + i][cb][h2] = Tr::mma(wf, bcur[h2], acc[1 + i][cb][h2]);
+                        __builtin_amdgcn_sched_group_barrier(0x002, 8, 0);
+                        __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+                    }
+                }
                 if (more) { bcur[0] = bnxt[0]; bcur[1] = bnxt[1]; }
+            } else {
+                // operand variants of this tile: W itself and W with mask i's gate elements negated
+                frag var[SETS][CB];
+    #pragma unroll
+                for (int cb = 0; cb < CB; ++cb) {
+                    var[0][cb] = aw[t][cb];
+                    if constexpr (MODE == kModeSwiglu) {
+                        var[1][cb] = aw2[t][cb];
+                    } else if constexpr (MODE != kModeLinear) {
+    #pragma unroll
+                        for (int i = 0; i < NMP; ++i) var[1 + i][cb] = Tr::template flip<NMP>(aw[t][cb], mk[MS][cb], t, i);
+                    }
+                }
+    #pragma unroll
+                for (int pi = 0; pi < PAIRS; ++pi) {
+                    const bool more = (pi + 1 < PAIRS) || (t + 1 < 4);
+                    if (more) {
+                        read_pair(bnxt, pi + 1 < PAIRS ? t : t + 1, pi + 1 < PAIRS ? pi + 1 : 0);
+                        asm volatile("s_waitcnt lgkmcnt(2)" : "+v"(bcur[0]), "+v"(bcur[1]));
+                    } else {
+                        asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(bcur[0]), "+v"(bcur[1]));
+                    }
+    #pragma unroll
+                    for (int h2 = 0; h2 < 2; ++h2)
+    #pragma unroll
+                        for (int s = 0; s < SETS; ++s)
+    #pragma unroll
+                            for (int cb = 0; cb < CB; ++cb)
+                                acc[s][cb][2 * pi + h2] = Tr::mma(var[s][cb], bcur[h2], acc[s][cb][2 * pi + h2]);
+                    if (more) { bcur[0] = bnxt[0]; bcur[1] = bnxt[1]; }
+                }
             }
 #pragma unroll
             for (int s = 0; s < XPIECES; ++s)   // a piece is stored one tile after its load was issued
@@ -337,14 +367,16 @@ static hipError_t launch_prefill_t(const PrefillParams &p, int mode, hipStream_t
         case 1: return launch_prefill_one<Tr, 1, 2, 8, kModeMgluVariant, 1>(p, stream);
         case 2: return launch_prefill_one<Tr, 2, 1, 8, kModeMgluVariant, 2>(p, stream);
         case 4: return launch_prefill_one<Tr, 4, 1, MGLU_PREFILL_TB4, kModeMgluVariant, MGLU_PREFILL_AD4>(p, stream);
-        default: return launch_prefill_one<Tr, 8, 1, 4, kModeMgluVariant, 2>(p, stream);
+        case 8: return launch_prefill_one<Tr, 8, 1, 4, kModeMgluVariant, 2>(p, stream);
+        default: return launch_prefill_one<Tr, 16, 1, 2, kModeMgluVariant, 2>(p, stream);
         }
     }
     switch (round_up_masks(p.n_masks)) {
     case 1: return launch_prefill_one<Tr, 1, 2, 8, kModeMglu, 1>(p, stream);
     case 2: return launch_prefill_one<Tr, 2, 1, 8, kModeMglu, 2>(p, stream);
     case 4: return launch_prefill_one<Tr, 4, 1, MGLU_PREFILL_TB4, kModeMglu, MGLU_PREFILL_AD4>(p, stream);
-    default: return launch_prefill_one<Tr, 8, 1, 4, kModeMglu, 2>(p, stream);
+    case 8: return launch_prefill_one<Tr, 8, 1, 4, kModeMglu, 2>(p, stream);
+    default: return launch_prefill_one<Tr, 16, 1, 2, kModeMglu, 2>(p, stream);
     }
 }
 

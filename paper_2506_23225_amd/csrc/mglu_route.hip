@@ -24,7 +24,6 @@ __device__ __forceinline__ float route_elem<_Float16>(const void *p, long i)
 template <typename elem_t>
 __global__ __launch_bounds__(256) void route_topk_kernel(RouteParams p)
 {
-    constexpr int kMaxMasks = 8;
     const int lane = threadIdx.x & 63;
     const int tok = blockIdx.x * 4 + (threadIdx.x >> 6);
     if (tok >= p.T) return;

@@ -97,11 +97,13 @@ __device__ __forceinline__ void load_wchunk(WChunk<Tr, NMP, MODE> &c, const char
         for (int t = 0; t < Tr::TILES; ++t) c.w2[t] = stream_load(reinterpret_cast<const frag *>(wp2 + t * 1024));
     } else if constexpr (MODE == kModeLinear) {
         (void)mp;
-    } else if constexpr (NMP == 8) {
-        u32x4 a = stream_load(reinterpret_cast<const u32x4 *>(mp));
-        u32x4 b = stream_load(reinterpret_cast<const u32x4 *>(reinterpret_cast<const char *>(mp) + kMaskHalfBytes));
+    } else if constexpr (NMP >= 8) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) { c.m[i] = a[i]; c.m[4 + i] = b[i]; }
+        for (int piece = 0; piece < NMP / 4; ++piece) {
+            u32x4 a = stream_load(reinterpret_cast<const u32x4 *>(reinterpret_cast<const char *>(mp) + piece * kMaskPieceBytes));
+#pragma unroll
+            for (int i = 0; i < 4; ++i) c.m[4 * piece + i] = a[i];
+        }
     } else if constexpr (NMP == 4) {
         u32x4 a = stream_load(reinterpret_cast<const u32x4 *>(mp));
 #pragma unroll
@@ -428,10 +430,6 @@ void stream_panel_kernel(StreamParams p)
     for (int st = 0; st < SETS; ++st)
 #pragma unroll
         for (int tb = 0; tb < TB; ++tb) acc[st][tb] = f32x4{0.f, 0.f, 0.f, 0.f};
-    float rw[TB][NMP];
-#pragma unroll
-    for (int tb = 0; tb < TB; ++tb)
-        route_weights<NMP>(epilogue_params<MODE>(p), tok0 + 16 * tb + r, s == 0 && tok0 + 16 * tb + r < p.T, rw[tb]);
 
     const int n_panels = (p.NC + NWK * CPW - 1) / (NWK * CPW);
     auto load_chunk = [&](chunk_t &ck, int g) __attribute__((always_inline)) {
@@ -539,13 +537,21 @@ void stream_panel_kernel(StreamParams p)
                         acc[st][tb] += lds[(((c * (NWK - 1) + w - 1) * SETS + st) * TB + tb) * kWave + lane];
         }
     }
-    if (s == 0 && jb < p.NB) epilogue<Tr, NMP, TB, MODE>(p, acc, rw, jb, tok0, r, q);
+    if (s == 0 && jb < p.NB) {
+        // route weights: read here, not ahead of the K loop (this kernel has no registers to hold them
+        // across it, and its workgroups run long enough that the read's latency does not show)
+        float rw[TB][NMP];
+#pragma unroll
+        for (int tb = 0; tb < TB; ++tb)
+            route_weights<NMP>(epilogue_params<MODE>(p), tok0 + 16 * tb + r, tok0 + 16 * tb + r < p.T, rw[tb]);
+        epilogue<Tr, NMP, TB, MODE>(p, acc, rw, jb, tok0, r, q);
+    }
 }
 
 // ---- host side --------------------------------------------------------------------------------
 
 // Largest token-block count per workgroup the 256-register budget allows in the panel kernel.
-int stream_max_token_blocks(int nmp, int elem) { return elem == kElemF32 ? 1 : nmp <= 2 ? 4 : 2; }
+int stream_max_token_blocks(int nmp, int elem) { return elem == kElemF32 || nmp > 8 ? 1 : nmp <= 2 ? 4 : 2; }
 
 struct PanelWide  { static constexpr int NWC = 8, NWK = 1, CPW = 2; };
 struct PanelSplit { static constexpr int NWC = 4, NWK = 2, CPW = 1; };
@@ -629,7 +635,7 @@ static hipError_t launch_panel(const StreamParams &p, const StreamPlan &pl, hipS
     constexpr bool kIsBf16 = Tr::ELEM_BYTES == 2;
     constexpr int NWC = Shape::NWC, NWK = Shape::NWK, CPW = Shape::CPW;
     if (pl.tb == 1) return launch_kernel(stream_panel_kernel<Tr, NMP, 1, MODE, NWC, NWK, CPW>, p, pl, stream);
-    if constexpr (kIsBf16) {
+    if constexpr (kIsBf16 && NMP <= 8) {
         if (pl.tb == 2) return launch_kernel(stream_panel_kernel<Tr, NMP, 2, MODE, NWC, NWK, CPW>, p, pl, stream);
         if constexpr (NMP <= 2) {
             if (pl.tb == 4) return launch_kernel(stream_panel_kernel<Tr, NMP, 4, MODE, NWC, NWK, CPW>, p, pl, stream);
@@ -653,7 +659,8 @@ static hipError_t launch_nmp(const StreamParams &p, int nmp, const StreamPlan &p
     case 1: return launch_plan<Tr, 1, MODE>(p, pl, s);
     case 2: return launch_plan<Tr, 2, MODE>(p, pl, s);
     case 4: return launch_plan<Tr, 4, MODE>(p, pl, s);
-    default: return launch_plan<Tr, 8, MODE>(p, pl, s);
+    case 8: return launch_plan<Tr, 8, MODE>(p, pl, s);
+    default: return launch_plan<Tr, 16, MODE>(p, pl, s);
     }
 }
 

@@ -51,7 +51,7 @@ def test_bad_arguments_are_reported_not_launched(lib):
     assert fwd(ok, x=None) == INVALID and b"x_dev" in lib.mglu_last_error()
     assert fwd(ok, out=ctypes.c_void_p(0x1004)) == INVALID and b"aligned" in lib.mglu_last_error()
     for field, value, code in (("tokens", 0, INVALID), ("d_model", 0, INVALID), ("d_ff", -1, INVALID),
-                               ("n_masks", 0, INVALID), ("n_masks", 9, UNSUPPORTED),
+                               ("n_masks", 0, INVALID), ("n_masks", 17, UNSUPPORTED),
                                ("dtype", 7, INVALID), ("w_layout", 2, INVALID), ("d_model", 100, UNSUPPORTED)):
         bad = _lib.MgluDesc(1, 256, 64, 2, _lib.MGLU_BF16, _lib.MGLU_W_KN)
         setattr(bad, field, value)

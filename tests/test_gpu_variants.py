@@ -112,6 +112,21 @@ def test_routed_layer_hand_made_weights(dtype):
                                                 route_weights=w[:1].contiguous()), single)
 
 
+@pytest.mark.parametrize("T", [1, 8, 48, 100])
+def test_sixteen_masks_routed_top4_gelu(T):
+    """16 masks, top-4 routing from the GPU router, GELU gate: router, compaction and epilogue at the widest."""
+    h, d, n_m = 512, 96, 16
+    x, W, masks = synth.make_inputs(h, d, n_m, T, dtype="bf16", seed=300 + T, device=DEV)
+    gen = torch.Generator(device=DEV).manual_seed(7)
+    Wr = (torch.randn(h, n_m, generator=gen, device=DEV) * 0.1).to(x.dtype)
+    desc, Wp, Mp = _packed(x, W, masks)
+    w = api.mglu_route_topk(desc, x, Wr, 4)
+    assert torch.all((w > 0).sum(dim=1) == 4)
+    out = api.mglu_forward_variant(desc, x, Wp, Mp, gate="gelu", route_weights=w)
+    ref = oracle.mglu_forward_variant(to_np64(x), to_np64(W), masks.cpu().numpy(), gate="gelu", route=to_np64(w))
+    assert rel_err(to_np64(out), ref) <= TOL[x.dtype]
+
+
 @pytest.mark.parametrize("dtype,T", [("bf16", 1), ("bf16", 32), ("bf16", 200), ("f32", 3), ("f16", 5), ("f16", 120)])
 def test_linear_projection(dtype, T):
     K, N = 656, 272
