@@ -12,7 +12,9 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libmglu.so")
-SOURCES = ["mglu_api.hip", "mglu_pack.hip", "mglu_stream.hip", "mglu_prefill.hip", "mglu_route.hip"]
+# the heavy files first: the kernels are instantiated per element type in files of their own so that they compile side by side
+SOURCES = ["mglu_stream_bf16.hip", "mglu_stream_f16.hip", "mglu_stream_f32.hip", "mglu_prefill_bf16.hip",
+           "mglu_prefill_f16.hip", "mglu_api.hip", "mglu_pack.hip", "mglu_stream.hip", "mglu_prefill.hip", "mglu_route.hip"]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wextra",
     "-Wno-unused-command-line-argument",
@@ -59,7 +61,7 @@ def build(force=True, verbose=False, extra_flags=(), lib=LIB, obj_dir=OBJ):
             print(res.stderr, file=sys.stderr)
         return obj
 
-    with ThreadPoolExecutor(max_workers=4) as pool:
+    with ThreadPoolExecutor(max_workers=min(8, os.cpu_count() or 4)) as pool:
         objs = list(pool.map(compile_one, sources))
     tmp = lib + ".tmp.%d" % os.getpid()
     cmd = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", tmp, *objs]

@@ -54,7 +54,6 @@ struct PackParams {
 
 // `elem` is an Elem (mglu_common.hpp): the element type of x, W and out
 hipError_t launch_stream(const StreamParams &p, int elem, int mode, hipStream_t stream);
-int stream_max_token_blocks(int nmp, int elem);
 hipError_t launch_stream_read(const void *buf, size_t bytes, uint32_t *sink, hipStream_t stream);
 
 hipError_t launch_prefill(const PrefillParams &p, int elem, int mode, hipStream_t stream);   // 16-bit elements only

@@ -1,0 +1,384 @@
+// MFMA-tiled MGLU kernel for prefill / large batches (bf16): compute-bound.
+//
+// The paper has no batched kernel; what it states for this regime is the cost model
+// (Discussion, "Computational Cost": one dense contraction plus one per mask).  The layer
+// is Eq. 3; the complement trick of Alg. 1 carries over: per output tile the kernel keeps
+// 1 + n_m accumulator sets, t = x W and dsum_i = x (W with the sign of every gate element
+// flipped), and the epilogue forms gate_i = (t - dsum_i)/2, value_i = (t + dsum_i)/2,
+// sum_i swish(gate_i) * value_i in registers.  So the matrix cores do (1 + n_m) GEMMs'
+// worth of work instead of the 2 n_m of the naive form, and W, the masks and x are each
+// staged once per tile for all of them.
+//
+// Tiling (one workgroup = 8 wavefronts = one CU at 2 wavefronts per SIMD):
+//   workgroup tile  BM = 16*TB tokens  x  BN = 8*16*CB columns
+//   wavefront w owns CB column blocks of 16 columns, for all BM tokens
+//   A operand (W): streamed straight from global memory in the packed tile order -- each
+//     wavefront reads only its own column blocks, so LDS staging would buy no reuse
+//   masks: read next to W, one chunk (128 k) of words at a time, applied in registers
+//   B operand (x): shared by all 8 wavefronts -> staged through LDS in B-fragment order,
+//     double-buffered per 128-k chunk, one barrier per chunk
+//   MFMA: v_mfma_f32_16x16x32_bf16, 16 columns x 16 tokens per accumulator
+// Workgroup ids are remapped so that the workgroups resident on one XCD (ids equal mod 8)
+// cover a compact patch of tiles and share W / x through that XCD's L2.
+#pragma once
+#include <type_traits>
+
+#include "mglu_common.hpp"
+#include "mglu_kernels.hpp"
+
+// Tile shapes per mask count, chosen so that the accumulators plus the operand ring stay
+// inside the 256 registers a wavefront has at 2 wavefronts per SIMD (no scratch).
+#ifndef MGLU_PREFILL_AD4
+#define MGLU_PREFILL_AD4 2
+#endif
+#ifndef MGLU_PREFILL_TB4
+#define MGLU_PREFILL_TB4 6   // token blocks per workgroup tile for four masks
+#endif
+
+namespace mglu {
+
+// In which tile of a chunk the s-th x piece of the next chunk is loaded / written to LDS.
+#ifndef MGLU_PREFILL_XLOAD_TILE
+#define MGLU_PREFILL_XLOAD_TILE(s, n) ((s) * 3 / (n))
+#define MGLU_PREFILL_XSTORE_TILE(s, n) ((s) * 3 / (n) + 1)
+#endif
+#ifndef MGLU_PREFILL_WAVES
+#define MGLU_PREFILL_WAVES 8   // wavefronts per workgroup (8: one workgroup per CU; 4: two)
+#endif
+constexpr int kPrefillWaves = MGLU_PREFILL_WAVES;
+
+// AD: how many tiles ahead of the multiply the A fragments are fetched.
+template <typename Tr, int NMP, int CB, int TB, int MODE, int AD>
+__global__ __launch_bounds__(kPrefillWaves *kWave) __attribute__((amdgpu_waves_per_eu(2, 2)))
+void prefill_kernel(PrefillParams p)
+{
+    typedef typename Tr::frag frag;
+    constexpr int SETS = sets_of(MODE, NMP);
+    constexpr int AR = 4;                       // ring entries (one per tile of a chunk)
+    constexpr long CHUNK_BYTES = (long)kColBlock * kChunkK * 2;
+    constexpr int XPIECES = TB * 4 / kPrefillWaves;  // x fragments each wavefront stages per chunk
+    static_assert(TB * 4 % kPrefillWaves == 0, "token blocks must split evenly over the wavefronts");
+    extern __shared__ f32x4 lds_raw[];
+    frag *lds_x = reinterpret_cast<frag *>(lds_raw);   // [2][tile t<4][tb<TB][lane<64]
+    // byte address of that array inside LDS, for the hand-placed reads
+    const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char *)lds_raw;
+
+    const int lane = threadIdx.x & 63;
+    // the wavefront index is uniform over the wavefront: say so, and every address below splits into
+    // a scalar base plus a 32-bit per-lane offset (no 64-bit vector arithmetic per load)
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int r = lane & 15, q = lane >> 4;
+    const uint32_t lane16 = lane * 16;
+
+    // ---- XCD-aware tile order: ids equal mod 8 share an L2; give each XCD a band of column
+    //      tiles and walk it in patches of p.group_m token tiles ----
+    int tile_m, tile_n;
+    {
+        const int wg = blockIdx.x;
+        const int xcd = wg & 7, local = wg >> 3;
+        const int per_xcd = (p.tiles_n + 7) >> 3;         // column tiles per XCD band
+        const int gm = p.group_m;
+        const int patch = local / (gm * per_xcd);          // which group of token tiles
+        const int in_patch = local - patch * gm * per_xcd;
+        const int m0 = patch * gm;
+        const int rows = min(gm, p.tiles_m - m0);          // last patch may be short
+        tile_m = m0 + in_patch % rows;
+        tile_n = xcd * per_xcd + in_patch / rows;
+        if (tile_m >= p.tiles_m || tile_n >= p.tiles_n || in_patch / rows >= per_xcd) return;
+    }
+    const int tok0 = tile_m * (16 * TB);
+    const int jb0 = (tile_n * kPrefillWaves + wave) * CB;   // first column block of this wavefront
+
+    // column blocks past the end are clamped for the loads and dropped at the store
+    const char *wbase[CB];       // scalar: start of the column block's weight stream
+    const char *w2base[CB];
+    const char *mbase[CB];       // scalar: start of its mask words
+#pragma unroll
+    for (int cb = 0; cb < CB; ++cb) {
+        const long jb = min(jb0 + cb, p.NB - 1);
+        wbase[cb] = static_cast<const char *>(p.w) + jb * p.NC * CHUNK_BYTES;
+        w2base[cb] = static_cast<const char *>(p.w2) + jb * p.NC * CHUNK_BYTES;
+        mbase[cb] = reinterpret_cast<const char *>(p.m) + jb * p.NC * (kWave * NMP * 4);
+    }
+    const uint32_t lane_m = mask_lane_bytes<NMP>(lane);
+
+    f32x4 acc[SETS][CB][TB];
+#pragma unroll
+    for (int s = 0; s < SETS; ++s)
+#pragma unroll
+        for (int cb = 0; cb < CB; ++cb)
+#pragma unroll
+            for (int tb = 0; tb < TB; ++tb) acc[s][cb][tb] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    // ---- x staging: wavefront w copies fragments idx = w + NW s (idx = tb * 4 + t) of a chunk:
+    //      lane (r, q) moves x[tok0 + 16 tb + r][128 kc + 32 t + 8 q .. + 8) to LDS slot
+    //      (t * TB + tb) * 64 + lane, the order the B operand is read in.  Token rows past T are
+    //      clamped to the last row (their outputs are never stored) and k past d_model to the
+    //      row's last fragment (W is zero-padded there, so whatever finite x is read adds 0). ----
+    const char *xbase = static_cast<const char *>(p.x) + (long)tok0 * p.h * 2;   // scalar
+    const uint32_t klim = (uint32_t)(p.h - 8) * 2;
+    uint32_t xrow[XPIECES];      // per piece: byte offset of this lane's token row from xbase
+#pragma unroll
+    for (int s = 0; s < XPIECES; ++s) {
+        const int tb = (wave + kPrefillWaves * s) >> 2;
+        xrow[s] = (uint32_t)(min(tok0 + 16 * tb + r, p.T - 1) - tok0) * (uint32_t)(p.h * 2);
+    }
+    auto x_src = [&](int kc, int s) __attribute__((always_inline)) {
+        const int t = (wave + kPrefillWaves * s) & 3;
+        const uint32_t kb = min((uint32_t)(kc * kChunkK + 32 * t) * 2 + q * 16, klim);
+        return reinterpret_cast<const frag *>(xbase + (xrow[s] + kb));
+    };
+    auto x_dst = [&](int buf, int s) __attribute__((always_inline)) {
+        const int idx = wave + kPrefillWaves * s;
+        const int tb = idx >> 2, t = idx & 3;
+        return lds_x + ((buf * 4 + t) * TB + tb) * kWave + lane;
+    };
+
+    // ---- A ring: entry t holds the fragments of tile t of the current (or next) chunk ----
+    frag aw[AR][CB];
+    frag aw2[MODE == kModeSwiglu ? AR : 1][CB];
+    uint32_t mk[2][CB][NMP];   // mask words of the current and the next chunk
+
+    auto load_a = [&](int kc, int t, int slot) __attribute__((always_inline)) {
+#pragma unroll
+        for (int cb = 0; cb < CB; ++cb) {
+            aw[slot][cb] = *reinterpret_cast<const frag *>(wbase[cb] + (long)kc * CHUNK_BYTES + t * 1024 + lane16);
+            if constexpr (MODE == kModeSwiglu)
+                aw2[slot][cb] =
+                    *reinterpret_cast<const frag *>(w2base[cb] + (long)kc * CHUNK_BYTES + t * 1024 + lane16);
+        }
+    };
+    auto load_masks = [&](int kc, int slot) __attribute__((always_inline)) {
+        if constexpr (MODE != kModeSwiglu && MODE != kModeLinear) {
+#pragma unroll
+            for (int cb = 0; cb < CB; ++cb) {
+                const uint32_t *mp =
+                    reinterpret_cast<const uint32_t *>(mbase[cb] + (long)kc * (kWave * NMP * 4) + lane_m);
+                if constexpr (NMP >= 8) {
+#pragma unroll
+                    for (int piece = 0; piece < NMP / 4; ++piece) {
+                        u32x4 a = *reinterpret_cast<const u32x4 *>(reinterpret_cast<const char *>(mp) + piece * kMaskPieceBytes);
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) mk[slot][cb][4 * piece + i] = a[i];
+                    }
+                } else if constexpr (NMP == 4) {
+                    u32x4 a = *reinterpret_cast<const u32x4 *>(mp);
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) mk[slot][cb][i] = a[i];
+                } else if constexpr (NMP == 2) {
+                    u32x2 a = *reinterpret_cast<const u32x2 *>(mp);
+                    mk[slot][cb][0] = a.x; mk[slot][cb][1] = a.y;
+                } else {
+                    mk[slot][cb][0] = *mp;
+                }
+            }
+        }
+    };
+
+    // ---- prologue: stage chunk 0 of x, start the A ring and the masks ----
+    const int last = p.NC - 1;
+    {
+        frag xv[XPIECES];
+#pragma unroll
+        for (int s = 0; s < XPIECES; ++s) xv[s] = *x_src(0, s);
+        load_masks(0, 0);
+#pragma unroll
+        for (int t = 0; t < AD; ++t) load_a(0, t, t);
+#pragma unroll
+        for (int s = 0; s < XPIECES; ++s) *x_dst(0, s) = xv[s];
+    }
+    __syncthreads();
+
+    // One chunk of the K loop; MS = which half of mk[] holds this chunk's masks (compile time).
+    auto chunk_step = [&](int kc, auto ms_tag) __attribute__((always_inline)) {
+        constexpr int MS = decltype(ms_tag)::value;
+        const int buf = kc & 1;
+        const int kn = min(kc + 1, last);   // next chunk, clamped: its loads are then always in bounds
+        frag xv[XPIECES];
+        // B fragments are read from LDS one pair of token blocks ahead of the MFMAs that use them
+        // (the compiler, left alone, issues each read right before its use and eats the LDS latency
+        // three times per tile).  The first pair of a chunk cannot be fetched before the barrier.
+        constexpr int PAIRS = TB / 2;
+        static_assert(TB % 2 == 0, "token blocks are processed in pairs");
+        // The reads are written as assembly so that they stay where they are put; the matching
+        // waits name the registers they release, which orders every use after them.  (lgkmcnt
+        // counts LDS operations in order, so "at most 2 newer ones outstanding" means the pair
+        // before them has landed; anything else in flight only makes the wait stricter.)
+        const uint32_t xchunk = lds_base + (uint32_t)(buf * 4 * TB * kWave + lane) * 16u;
+        auto read_pair = [&](frag (&b)[2], int t, int pi) __attribute__((always_inline)) {
+            asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(b[0]) : "v"(xchunk), "n"((t * TB + 2 * pi) * 1024));
+            asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(b[1]) : "v"(xchunk), "n"((t * TB + 2 * pi + 1) * 1024));
+        };
+        frag bcur[2], bnxt[2];
+        read_pair(bcur, 0, 0);
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            // Issue this tile's prefetches first: pieces of the next chunk's x (stored one tile
+            // later), the A fragments AD tiles ahead, and once per chunk the next chunk's masks.
+            // The scheduling fence keeps the compiler from sinking these loads down to their
+            // first use, which would expose the whole memory latency.
+#pragma unroll
+            for (int s = 0; s < XPIECES; ++s)
+                if (MGLU_PREFILL_XLOAD_TILE(s, XPIECES) == t) xv[s] = *x_src(kn, s);
+            if (t + AD < 4) load_a(kc, t + AD, (t + AD) % AR);
+            else load_a(kn, t + AD - 4, (t + AD) % AR);
+            if (t == 0) load_masks(kn, MS ^ 1);
+            __builtin_amdgcn_sched_barrier(0);
+
+            if constexpr (TB == 2 && MODE != kModeSwiglu && MODE != kModeLinear) {
+                // Many masks, one pair of token blocks: each mask's operand is prepared right before its
+                // two MFMAs and dropped after them (all variants at once would not fit the registers);
+                // the issue-order groups keep the compiler from gathering the preparation up front.
+                const bool more = t + 1 < 4;
+                if (more) {
+                    read_pair(bnxt, t + 1, 0);
+                    asm volatile("s_waitcnt lgkmcnt(2)" : "+v"(bcur[0]), "+v"(bcur[1]));
+                } else {
+                    asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(bcur[0]), "+v"(bcur[1]));
+                }
+#pragma unroll
+                for (int cb = 0; cb < CB; ++cb) {
+#pragma unroll
+                    for (int h2 = 0; h2 < 2; ++h2) acc[0][cb][h2] = Tr::mma(aw[t][cb], bcur[h2], acc[0][cb][h2]);
+                    __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+#pragma unroll
+                    for (int i = 0; i < NMP; ++i) {
+                        const frag wf = Tr::template flip<NMP>(aw[t][cb], mk[MS][cb], t, i);
+#pragma unroll
+                        for (int h2 = 0; h2 < 2; ++h2) acc[1 + i][cb][h2] = Tr::mma(wf, bcur[h2], acc[1 + i][cb][h2]);
+                        __builtin_amdgcn_sched_group_barrier(0x002, 8, 0);
+                        __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+                    }
+                }
+                if (more) { bcur[0] = bnxt[0]; bcur[1] = bnxt[1]; }
+            } else {
+                // operand variants of this tile: W itself and W with mask i's gate elements negated
+                frag var[SETS][CB];
+    #pragma unroll
+                for (int cb = 0; cb < CB; ++cb) {
+                    var[0][cb] = aw[t][cb];
+                    if constexpr (MODE == kModeSwiglu) {
+                        var[1][cb] = aw2[t][cb];
+                    } else if constexpr (MODE != kModeLinear) {
+    #pragma unroll
+                        for (int i = 0; i < NMP; ++i) var[1 + i][cb] = Tr::template flip<NMP>(aw[t][cb], mk[MS][cb], t, i);
+                    }
+                }
+    #pragma unroll
+                for (int pi = 0; pi < PAIRS; ++pi) {
+                    const bool more = (pi + 1 < PAIRS) || (t + 1 < 4);
+                    if (more) {
+                        read_pair(bnxt, pi + 1 < PAIRS ? t : t + 1, pi + 1 < PAIRS ? pi + 1 : 0);
+                        asm volatile("s_waitcnt lgkmcnt(2)" : "+v"(bcur[0]), "+v"(bcur[1]));
+                    } else {
+                        asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(bcur[0]), "+v"(bcur[1]));
+                    }
+    #pragma unroll
+                    for (int h2 = 0; h2 < 2; ++h2)
+    #pragma unroll
+                        for (int s = 0; s < SETS; ++s)
+    #pragma unroll
+                            for (int cb = 0; cb < CB; ++cb)
+                                acc[s][cb][2 * pi + h2] = Tr::mma(var[s][cb], bcur[h2], acc[s][cb][2 * pi + h2]);
+                    if (more) { bcur[0] = bnxt[0]; bcur[1] = bnxt[1]; }
+                }
+            }
+#pragma unroll
+            for (int s = 0; s < XPIECES; ++s)   // a piece is stored one tile after its load was issued
+                if (MGLU_PREFILL_XSTORE_TILE(s, XPIECES) == t) *x_dst(buf ^ 1, s) = xv[s];
+        }
+        __syncthreads();
+    };
+
+    int kc = 0;
+    for (; kc + 1 < p.NC; kc += 2) {
+        chunk_step(kc, std::integral_constant<int, 0>{});
+        chunk_step(kc + 1, std::integral_constant<int, 1>{});
+    }
+    if (kc < p.NC) chunk_step(kc, std::integral_constant<int, 0>{});
+
+    // ---- epilogue (Eq. 3): lane (r, q) holds token 16 tb + r, columns 4 q .. 4 q + 3 of each block ----
+#pragma unroll
+    for (int cb = 0; cb < CB; ++cb) {
+        const int jb = jb0 + cb;
+        if (jb >= p.NB) continue;
+        const int j0 = jb * kColBlock + 4 * q;
+        if (j0 >= p.d) continue;
+        const bool full = (j0 + 3 < p.d) && ((p.d & 3) == 0);
+#pragma unroll
+        for (int tb = 0; tb < TB; ++tb) {
+            const long tok = (long)tok0 + 16 * tb + r;
+            if (tok >= p.T) continue;
+            const EpilogueParams ep = MODE == kModeMgluVariant
+                                          ? EpilogueParams{p.n_masks, p.gate_fn, p.mask_use, p.route}
+                                          : EpilogueParams{p.n_masks, 0, 0, nullptr};
+            float rw[NMP];
+            route_weights<NMP>(ep, tok, true, rw);
+            f32x4 y;
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                if constexpr (MODE == kModeSwiglu) {
+                    y[c] = swish(acc[0][cb][tb][c]) * acc[1][cb][tb][c];
+                } else if constexpr (MODE == kModeLinear) {
+                    y[c] = acc[0][cb][tb][c];
+                } else {
+                    float ds[NMP];
+#pragma unroll
+                    for (int i = 0; i < NMP; ++i) ds[i] = acc[1 + i][cb][tb][c];
+                    y[c] = mglu_mix<NMP>(ep, rw, acc[0][cb][tb][c], ds);
+                }
+            }
+            const long o = tok * p.d + j0;
+            if (full) {
+                Tr::store4(p.out, o, y);
+            } else {
+#pragma unroll
+                for (int c = 0; c < 4; ++c)
+                    if (j0 + c < p.d) Tr::store1(p.out, o + c, y[c]);
+            }
+        }
+    }
+}
+
+// ---- host side --------------------------------------------------------------------------------
+
+template <typename Tr, int NMP, int CB, int TB, int MODE, int AD>
+static hipError_t launch_prefill_one(PrefillParams p, hipStream_t stream)
+{
+    const int bm = 16 * TB, bn = kPrefillWaves * kColBlock * CB;
+    p.tiles_m = (int)ceil_div(p.T, bm);
+    p.tiles_n = (int)ceil_div(p.d, bn);
+    p.group_m = p.tiles_m < 8 ? p.tiles_m : 8;
+    // every XCD gets per_xcd column tiles x tiles_m token tiles; ids beyond a band's end return at once
+    const int per_xcd = (p.tiles_n + 7) / 8;
+    const long wgs = (long)8 * per_xcd * p.tiles_m;
+    const size_t lds = (size_t)2 * 4 * TB * kWave * sizeof(f32x4);
+    auto kern = prefill_kernel<Tr, NMP, CB, TB, MODE, AD>;
+    hipLaunchKernelGGL(kern, dim3((unsigned)wgs), dim3(kPrefillWaves * kWave), lds, stream, p);
+    return hipGetLastError();
+}
+
+template <typename Tr>
+static hipError_t launch_prefill_t(const PrefillParams &p, int mode, hipStream_t stream)
+{
+    if (mode == kModeSwiglu) return launch_prefill_one<Tr, 1, 2, 8, kModeSwiglu, 1>(p, stream);
+    if (mode == kModeLinear) return launch_prefill_one<Tr, 1, 2, 8, kModeLinear, 2>(p, stream);
+    if (mode == kModeMgluVariant) {
+        switch (round_up_masks(p.n_masks)) {
+        case 1: return launch_prefill_one<Tr, 1, 2, 8, kModeMgluVariant, 1>(p, stream);
+        case 2: return launch_prefill_one<Tr, 2, 1, 8, kModeMgluVariant, 2>(p, stream);
+        case 4: return launch_prefill_one<Tr, 4, 1, MGLU_PREFILL_TB4, kModeMgluVariant, MGLU_PREFILL_AD4>(p, stream);
+        case 8: return launch_prefill_one<Tr, 8, 1, 4, kModeMgluVariant, 2>(p, stream);
+        default: return launch_prefill_one<Tr, 16, 1, 2, kModeMgluVariant, 2>(p, stream);
+        }
+    }
+    switch (round_up_masks(p.n_masks)) {
+    case 1: return launch_prefill_one<Tr, 1, 2, 8, kModeMglu, 1>(p, stream);
+    case 2: return launch_prefill_one<Tr, 2, 1, 8, kModeMglu, 2>(p, stream);
+    case 4: return launch_prefill_one<Tr, 4, 1, MGLU_PREFILL_TB4, kModeMglu, MGLU_PREFILL_AD4>(p, stream);
+    case 8: return launch_prefill_one<Tr, 8, 1, 4, kModeMglu, 2>(p, stream);
+    default: return launch_prefill_one<Tr, 16, 1, 2, kModeMglu, 2>(p, stream);
+    }
+}
+
+}  // namespace mglu
