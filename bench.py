@@ -223,6 +223,22 @@ def main():
         result["plain_read_same_bytes"] = {"ms": small_ms, "GBps": n_small / small_ms / 1e6,
                                            "note": "events around back-to-back launches; at this size the "
                                                    "host's launch rate and the kernel time are about equal"}
+        # the same cold-ring steps captured once into a HIP graph and replayed: launch gaps of the host gone
+        gsteps = 4 * head.copies
+        cap = torch.cuda.Stream()
+        cap.wait_stream(torch.cuda.current_stream())
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(cap):
+            head.step(0)
+            cap.synchronize()
+            with torch.cuda.graph(graph, stream=cap):
+                for i in range(gsteps):
+                    head.step(i)
+        torch.cuda.current_stream().wait_stream(cap)
+        graph_ms, _ = time_steps(torch, lambda i: graph.replay(), 20, 3)
+        result["graph_replay"] = {"ms_per_step": graph_ms / gsteps, "GBps": head.bytes / (graph_ms / gsteps) / 1e6,
+                                  "steps_per_graph": gsteps}
+        del graph
         result["warm_cache"] = {"ms": warm_ms, "GBps": head.bytes / warm_ms / 1e6}
         result["swiglu_reference"] = {"ms": sw_ms, "GBps": head.glu_bytes / sw_ms / 1e6,
                                       "mglu_over_swiglu_time": ms / sw_ms,
