@@ -39,6 +39,9 @@
 #ifndef MGLU_STREAM_RING
 #define MGLU_STREAM_RING 2        // resident kernel: chunks of W a wavefront keeps in flight
 #endif
+#ifndef MGLU_RESIDENT_MAX_T
+#define MGLU_RESIDENT_MAX_T 16    // most tokens the resident kernel takes (the panel kernel takes the rest)
+#endif
 #ifndef MGLU_STREAM_NONTEMPORAL
 #define MGLU_STREAM_NONTEMPORAL 1 // W and the masks are read once per call: mark the loads streaming
 #endif
@@ -583,7 +586,7 @@ static StreamPlan plan_stream(const StreamParams &p, int elem_kind, int nmp, int
     const int nw = 1 << nw_shift;
     const size_t red = nw > 1 ? (size_t)(nw - 1) * sets * 4 * tc * sizeof(f32x4) : 0;
     const size_t xb = (size_t)resident_x_frags_padded((p.NC * tiles * 4) << resident_row_shift(tc), nw_shift) * 16;
-    if (p.T <= 16 && xb + red <= kLdsBudget) {
+    if (p.T <= MGLU_RESIDENT_MAX_T && xb + red <= kLdsBudget) {
         pl.resident = true;
         pl.tb = 1;
         pl.nw = nw;
