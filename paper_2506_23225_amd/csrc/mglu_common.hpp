@@ -79,6 +79,15 @@ __device__ __forceinline__ float swish(float z)
 
 // ---- element traits ------------------------------------------------------------------------
 // A chunk is TILES fragments per lane; a fragment is 16 bytes of W (A operand) or x (B operand).
+// 64-bit left shift as one instruction.  Written as assembly because the compiler, seeing that only
+// two bits of each half are used afterwards, narrows the C expression back to two 32-bit shifts.
+__device__ __forceinline__ uint64_t shl64(uint64_t v, int s)
+{
+    uint64_t r;
+    asm("v_lshlrev_b64 %0, %1, %2" : "=v"(r) : "s"(s), "v"(v));
+    return r;
+}
+
 // 16-bit elements, two to a register.  bf16 and fp16 share the fragment shapes and -- the sign bit
 // being bit 15 of either format -- the mask application; they differ in the MFMA and the rounding.
 struct Half16Common {
@@ -89,30 +98,44 @@ struct Half16Common {
     static constexpr int ELEM_BYTES = 2;
 
     // W fragment of tile t with the sign of every element whose bit in mask i is set flipped.
+    // `i` may be a compile-time constant or a run-time value that is uniform over the wavefront
+    // (the word that holds a bit does not depend on i, only the shift does).
+    // With 8 or 16 masks two registers of the fragment take their bits from two neighbouring words
+    // at the same shift, so one 64-bit shift (full rate on gfx950) serves both: 6 vector-ALU
+    // instructions per fragment and mask instead of 8.
     template <int NMP>
     __device__ static __forceinline__ frag flip(frag w, const uint32_t (&m)[NMP], int t, int i)
     {
         frag r;
+        if constexpr (NMP == 8) {
+            // pair p: word 2t + p/2, bit (p%2)*8 + i
+            const uint64_t mm = ((uint64_t)m[2 * t + 1] << 32) | m[2 * t];
+            const uint64_t a = shl64(mm, 15 - i), b = shl64(mm, 7 - i);
+            r[0] = w[0] ^ ((uint32_t)a & 0x80008000u);
+            r[1] = w[1] ^ ((uint32_t)b & 0x80008000u);
+            r[2] = w[2] ^ ((uint32_t)(a >> 32) & 0x80008000u);
+            r[3] = w[3] ^ ((uint32_t)(b >> 32) & 0x80008000u);
+        } else if constexpr (NMP == 16) {
+            // pair p: word 4t + p, bit i
+            const uint64_t m01 = shl64(((uint64_t)m[4 * t + 1] << 32) | m[4 * t], 15 - i);
+            const uint64_t m23 = shl64(((uint64_t)m[4 * t + 3] << 32) | m[4 * t + 2], 15 - i);
+            r[0] = w[0] ^ ((uint32_t)m01 & 0x80008000u);
+            r[1] = w[1] ^ ((uint32_t)(m01 >> 32) & 0x80008000u);
+            r[2] = w[2] ^ ((uint32_t)m23 & 0x80008000u);
+            r[3] = w[3] ^ ((uint32_t)(m23 >> 32) & 0x80008000u);
+        } else {
 #pragma unroll
-        for (int p = 0; p < 4; ++p) {
-            const int lin = (4 * t + p) * NMP + i;
-            r[p] = w[p] ^ ((m[lin >> 4] << (15 - (lin & 15))) & 0x80008000u);
+            for (int p = 0; p < 4; ++p) {
+                const int lin0 = (4 * t + p) * NMP;
+                r[p] = w[p] ^ ((m[lin0 >> 4] << (15 - (lin0 & 15) - i)) & 0x80008000u);
+            }
         }
         return r;
     }
-
-    // The same with the mask index known only at run time (uniform over the wavefront): the word
-    // that holds the bit does not depend on i, only the shift does.
     template <int NMP>
     __device__ static __forceinline__ frag flip_at(frag w, const uint32_t (&m)[NMP], int t, int i)
     {
-        frag r;
-#pragma unroll
-        for (int p = 0; p < 4; ++p) {
-            const int lin0 = (4 * t + p) * NMP;
-            r[p] = w[p] ^ ((m[lin0 >> 4] << (15 - (lin0 & 15) - i)) & 0x80008000u);
-        }
-        return r;
+        return flip<NMP>(w, m, t, i);
     }
 };
 
