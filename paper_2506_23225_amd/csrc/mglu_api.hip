@@ -133,7 +133,7 @@ mglu::PackParams pack_params(const mglu_desc *d, const void *src, void *dst)
 
 extern "C" {
 
-int mglu_format_version(void) { return 2; }
+int mglu_format_version(void) { return 3; }
 
 size_t mglu_packed_weight_bytes(const mglu_desc *desc)
 {

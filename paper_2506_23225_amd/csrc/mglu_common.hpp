@@ -20,10 +20,12 @@
 //           so that every 16-byte-per-lane load of a wavefront is one contiguous 1 KiB run)
 //
 // A lane's NMP words hold the NMP x 32 mask bits of the 32 weight elements that
-// lane holds in the chunk.  bf16: the elements form 16 register pairs
-// P = 4t + e/2 (low half e even, high half e odd); bit for (P, mask i, half hf) is
-// at linear = P*NMP + i -> word linear/16, bit (linear%16) + 16*hf, so one shift
-// brings both bits of a pair to the two bf16 sign positions 15 and 31.
+// lane holds in the chunk.  16-bit elements: they form 16 register pairs (tile t, pair p = e/2; low
+// half e even, high half e odd); the bit for (t, p, mask i, half hf) is in word
+// Half16Common::mask_word(t, p) at position mask_bit(t, p, i) + 16*hf, so one shift brings both
+// bits of a pair to the two sign positions 15 and 31.  For 2 to 16 masks the words are
+// assigned so that registers p and p + 2 (16 masks: p and p + 1) of a fragment find their bits in
+// two neighbouring words at the same position: one 64-bit shift then serves both.
 // fp32: element E = 4t + e, linear = E*NMP + i -> word linear/32, bit linear%32.
 #pragma once
 #include <hip/hip_runtime.h>
@@ -123,14 +125,44 @@ struct Half16Common {
             r[1] = w[1] ^ ((uint32_t)(m01 >> 32) & 0x80008000u);
             r[2] = w[2] ^ ((uint32_t)m23 & 0x80008000u);
             r[3] = w[3] ^ ((uint32_t)(m23 >> 32) & 0x80008000u);
+        } else if constexpr (NMP == 4) {
+            // pair p: word 2(t/2) + p/2, bit ((t%2)*2 + p%2)*4 + i
+            const uint64_t mm = ((uint64_t)m[2 * (t / 2) + 1] << 32) | m[2 * (t / 2)];
+            const uint64_t a = shl64(mm, 15 - ((t % 2) * 8 + i)), b = shl64(mm, 15 - ((t % 2) * 8 + 4 + i));
+            r[0] = w[0] ^ ((uint32_t)a & 0x80008000u);
+            r[1] = w[1] ^ ((uint32_t)b & 0x80008000u);
+            r[2] = w[2] ^ ((uint32_t)(a >> 32) & 0x80008000u);
+            r[3] = w[3] ^ ((uint32_t)(b >> 32) & 0x80008000u);
+        } else if constexpr (NMP == 2) {
+            // pair p: word p/2, bit (t*2 + p%2)*2 + i
+            const uint64_t mm = ((uint64_t)m[1] << 32) | m[0];
+            const uint64_t a = shl64(mm, 15 - (t * 4 + i)), b = shl64(mm, 15 - (t * 4 + 2 + i));
+            r[0] = w[0] ^ ((uint32_t)a & 0x80008000u);
+            r[1] = w[1] ^ ((uint32_t)b & 0x80008000u);
+            r[2] = w[2] ^ ((uint32_t)(a >> 32) & 0x80008000u);
+            r[3] = w[3] ^ ((uint32_t)(b >> 32) & 0x80008000u);
         } else {
+            // one mask: pair p of tile t at bit 4t + p of the only word
 #pragma unroll
-            for (int p = 0; p < 4; ++p) {
-                const int lin0 = (4 * t + p) * NMP;
-                r[p] = w[p] ^ ((m[lin0 >> 4] << (15 - (lin0 & 15) - i)) & 0x80008000u);
-            }
+            for (int p = 0; p < 4; ++p) r[p] = w[p] ^ ((m[0] << (15 - (4 * t + p) - i)) & 0x80008000u);
         }
         return r;
+    }
+    // Where the pack kernel puts the bit of (tile t, pair p, mask i) of a lane: word index and bit
+    // position inside the low half of that word (the high half holds the pair's second element).
+    template <int NMP>
+    __host__ __device__ static constexpr int mask_word(int t, int p)
+    {
+        return NMP == 16 ? 4 * t + p : NMP == 8 ? 2 * t + p / 2 : NMP == 4 ? 2 * (t / 2) + p / 2 : NMP == 2 ? p / 2 : 0;
+    }
+    template <int NMP>
+    __host__ __device__ static constexpr int mask_bit(int t, int p, int i)
+    {
+        return NMP == 16 ? i
+             : NMP == 8  ? (p % 2) * 8 + i
+             : NMP == 4  ? ((t % 2) * 2 + p % 2) * 4 + i
+             : NMP == 2  ? (t * 2 + p % 2) * 2 + i
+                         : 4 * t + p;
     }
     template <int NMP>
     __device__ static __forceinline__ frag flip_at(frag w, const uint32_t (&m)[NMP], int t, int i)

@@ -72,9 +72,9 @@ __global__ __launch_bounds__(256) void pack_masks_kernel(PackParams p)
             for (int i = 0; i < NMP; ++i) {
                 if (i >= p.n_masks) break;
                 const uint32_t bit = src[i * plane + off] != 0 ? 1u : 0u;
-                if (Tr::ELEM_BYTES == 2) {
-                    const int lin = (4 * t + (e >> 1)) * NMP + i;  // register pair P = 4t + e/2
-                    words[lin >> 4] |= bit << ((lin & 15) + 16 * (e & 1));
+                if constexpr (Tr::ELEM_BYTES == 2) {
+                    words[Tr::template mask_word<NMP>(t, e >> 1)] |=
+                        bit << (Tr::template mask_bit<NMP>(t, e >> 1, i) + 16 * (e & 1));
                 } else {
                     const int lin = (4 * t + e) * NMP + i;         // element E = 4t + e
                     words[lin >> 5] |= bit << (lin & 31);
