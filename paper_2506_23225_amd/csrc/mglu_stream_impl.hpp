@@ -42,6 +42,12 @@
 #ifndef MGLU_RESIDENT_MAX_T
 #define MGLU_RESIDENT_MAX_T 16    // most tokens the resident kernel takes (the panel kernel takes the rest)
 #endif
+#ifndef MGLU_RESIDENT_RX
+#define MGLU_RESIDENT_RX 0        // resident kernel: read x from LDS in every lane (rows past T repeat the last one)
+#endif                            // instead of predicated; measured: -2 % on the smallest shape, +4 % on large ones
+#ifndef MGLU_RESIDENT_FLOOR
+#define MGLU_RESIDENT_FLOOR 1     // resident kernel: tell the register allocator how many wavefronts per SIMD to keep
+#endif
 #ifndef MGLU_STREAM_NONTEMPORAL
 #define MGLU_STREAM_NONTEMPORAL 1 // W and the masks are read once per call: mark the loads streaming
 #endif
@@ -216,8 +222,18 @@ __device__ __forceinline__ void epilogue(const StreamParams &p, const f32x4 (&ac
 // ones are delivered in scalar registers when the wavefront starts (kernel-argument preload,
 // switched on in the build flags), which takes one memory round trip off the start of every
 // workgroup.
+// Wavefronts per SIMD the register allocation must leave room for.  Told so, the compiler keeps the
+// accumulators of the 16-bit MGLU instantiations in ordinary registers and needs fewer in total
+// (8 masks: 120 instead of 88 + 72 accumulator registers), without spilling.
+__host__ __device__ constexpr int resident_min_waves(int elem_bytes, int mode, int nmp)
+{
+    if (!MGLU_RESIDENT_FLOOR || elem_bytes != 2 || mode == kModeSwiglu || mode == kModeLinear) return 1;
+    return nmp <= 1 ? 5 : nmp <= 4 ? 4 : nmp <= 8 ? 3 : 2;
+}
+
 template <typename Tr, int NMP, int MODE, int R>
-__global__ __launch_bounds__(MGLU_STREAM_MAX_WAVES *kWave) void stream_resident_kernel(
+__global__ __launch_bounds__(MGLU_STREAM_MAX_WAVES *kWave)
+__attribute__((amdgpu_waves_per_eu(resident_min_waves(Tr::ELEM_BYTES, MODE, NMP)))) void stream_resident_kernel(
     const void *a_w, const uint32_t *a_m, const void *a_x, int a_NC, int a_T, int a_h, int a_d, void *a_out,
     int a_nw_shift, int a_n_masks, int a_NB, const void *a_w2, float *a_proj_t, float *a_proj_gate, float *a_proj_value,
     int a_gate_fn, int a_mask_use, const float *a_route)
@@ -289,12 +305,15 @@ __global__ __launch_bounds__(MGLU_STREAM_MAX_WAVES *kWave) void stream_resident_
         load_wchunk<Tr, NMP, MODE>(c, wbase + (long)kc * CHUNK_BYTES, w2base + (long)kc * CHUNK_BYTES,
                                    mbase + (long)kc * kWave * NMP);
     };
+    // B-operand lanes past the last token: zero (predicated read), or with MGLU_RESIDENT_RX the last
+    // token's row again; either way their accumulator columns are never stored
+    const int rx = MGLU_RESIDENT_RX ? min(r, tc - 1) : r;
     auto compute = [&](const chunk_t &c, int kc) __attribute__((always_inline)) {
         if constexpr (MODE == kModeMgluVariant) {
 #pragma unroll
             for (int t = 0; t < Tr::TILES; ++t) {
                 frag xf = frag{0, 0, 0, 0};
-                if (r < tc) xf = lds_x[((((kc * Tr::TILES + t) * 4 + q)) << tsh) + r];
+                if (MGLU_RESIDENT_RX || r < tc) xf = lds_x[((((kc * Tr::TILES + t) * 4 + q)) << tsh) + rx];
                 acc[0][0] = Tr::mma(c.w[t], xf, acc[0][0]);
 #pragma unroll
                 for (int a = 0; a < NMP; ++a) {
@@ -306,7 +325,7 @@ __global__ __launch_bounds__(MGLU_STREAM_MAX_WAVES *kWave) void stream_resident_
 #pragma unroll
             for (int t = 0; t < Tr::TILES; ++t) {
                 frag xf[1] = {frag{0, 0, 0, 0}};
-                if (r < tc) xf[0] = lds_x[((((kc * Tr::TILES + t) * 4 + q)) << tsh) + r];
+                if (MGLU_RESIDENT_RX || r < tc) xf[0] = lds_x[((((kc * Tr::TILES + t) * 4 + q)) << tsh) + rx];
                 mma_tile<Tr, NMP, 1, MODE>(acc, c, t, xf);
             }
         }
