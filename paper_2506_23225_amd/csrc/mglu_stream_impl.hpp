@@ -42,9 +42,13 @@
 #ifndef MGLU_RESIDENT_MAX_T
 #define MGLU_RESIDENT_MAX_T 16    // most tokens the resident kernel takes (the panel kernel takes the rest)
 #endif
-#ifndef MGLU_RESIDENT_RX
-#define MGLU_RESIDENT_RX 0        // resident kernel: read x from LDS in every lane (rows past T repeat the last one)
-#endif                            // instead of predicated; measured: -2 % on the smallest shape, +4 % on large ones
+// Resident kernel, main form only: launches with at most this many chunks of W per CU run a flavour
+// that reads x from LDS in every lane (rows past T repeat the last one) instead of predicated.  The
+// compiler then fetches the fragments further ahead: measured 2-3 % faster on the 2048 x 5632 shape
+// (22 chunks per CU), 3-5 % slower from 4096 x 14336 (112 per CU) on.
+#ifndef MGLU_RESIDENT_RX_MAX_CHUNKS_PER_CU
+#define MGLU_RESIDENT_RX_MAX_CHUNKS_PER_CU 48
+#endif
 #ifndef MGLU_RESIDENT_FLOOR
 #define MGLU_RESIDENT_FLOOR 1     // resident kernel: tell the register allocator how many wavefronts per SIMD to keep
 #endif
@@ -231,7 +235,7 @@ __host__ __device__ constexpr int resident_min_waves(int elem_bytes, int mode, i
     return nmp <= 1 ? 5 : nmp <= 4 ? 4 : nmp <= 8 ? 3 : 2;
 }
 
-template <typename Tr, int NMP, int MODE, int R>
+template <typename Tr, int NMP, int MODE, int R, bool RX>
 __global__ __launch_bounds__(MGLU_STREAM_MAX_WAVES *kWave)
 __attribute__((amdgpu_waves_per_eu(resident_min_waves(Tr::ELEM_BYTES, MODE, NMP)))) void stream_resident_kernel(
     const void *a_w, const uint32_t *a_m, const void *a_x, int a_NC, int a_T, int a_h, int a_d, void *a_out,
@@ -305,15 +309,15 @@ __attribute__((amdgpu_waves_per_eu(resident_min_waves(Tr::ELEM_BYTES, MODE, NMP)
         load_wchunk<Tr, NMP, MODE>(c, wbase + (long)kc * CHUNK_BYTES, w2base + (long)kc * CHUNK_BYTES,
                                    mbase + (long)kc * kWave * NMP);
     };
-    // B-operand lanes past the last token: zero (predicated read), or with MGLU_RESIDENT_RX the last
+    // B-operand lanes past the last token: zero (predicated read), or in the RX flavour the last
     // token's row again; either way their accumulator columns are never stored
-    const int rx = MGLU_RESIDENT_RX ? min(r, tc - 1) : r;
+    const int rx = RX ? min(r, tc - 1) : r;
     auto compute = [&](const chunk_t &c, int kc) __attribute__((always_inline)) {
         if constexpr (MODE == kModeMgluVariant) {
 #pragma unroll
             for (int t = 0; t < Tr::TILES; ++t) {
                 frag xf = frag{0, 0, 0, 0};
-                if (MGLU_RESIDENT_RX || r < tc) xf = lds_x[((((kc * Tr::TILES + t) * 4 + q)) << tsh) + rx];
+                if (RX || r < tc) xf = lds_x[((((kc * Tr::TILES + t) * 4 + q)) << tsh) + rx];
                 acc[0][0] = Tr::mma(c.w[t], xf, acc[0][0]);
 #pragma unroll
                 for (int a = 0; a < NMP; ++a) {
@@ -325,7 +329,7 @@ __attribute__((amdgpu_waves_per_eu(resident_min_waves(Tr::ELEM_BYTES, MODE, NMP)
 #pragma unroll
             for (int t = 0; t < Tr::TILES; ++t) {
                 frag xf[1] = {frag{0, 0, 0, 0}};
-                if (MGLU_RESIDENT_RX || r < tc) xf[0] = lds_x[((((kc * Tr::TILES + t) * 4 + q)) << tsh) + rx];
+                if (RX || r < tc) xf[0] = lds_x[((((kc * Tr::TILES + t) * 4 + q)) << tsh) + rx];
                 mma_tile<Tr, NMP, 1, MODE>(acc, c, t, xf);
             }
         }
@@ -671,7 +675,13 @@ static hipError_t launch_panel(const StreamParams &p, const StreamPlan &pl, hipS
 template <typename Tr, int NMP, int MODE>
 static hipError_t launch_plan(const StreamParams &p, const StreamPlan &pl, hipStream_t stream)
 {
-    if (pl.resident) return launch_resident(stream_resident_kernel<Tr, NMP, MODE, MGLU_STREAM_RING>, p, pl, stream);
+    if (pl.resident) {
+        if constexpr (MODE == kModeMglu && Tr::ELEM_BYTES == 2) {
+            if ((long)p.NB * p.NC <= 256L * MGLU_RESIDENT_RX_MAX_CHUNKS_PER_CU)
+                return launch_resident(stream_resident_kernel<Tr, NMP, MODE, MGLU_STREAM_RING, true>, p, pl, stream);
+        }
+        return launch_resident(stream_resident_kernel<Tr, NMP, MODE, MGLU_STREAM_RING, false>, p, pl, stream);
+    }
     return pl.wide ? launch_panel<Tr, NMP, MODE, PanelWide>(p, pl, stream)
                    : launch_panel<Tr, NMP, MODE, PanelSplit>(p, pl, stream);
 }
