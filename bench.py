@@ -199,7 +199,7 @@ def main():
         "wall_ms_per_step": wall_ms,
         "roofline": {"bound": "hbm", "achieved": rec["GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": rec["hbm_frac"], "traffic": measured_traffic("decode_gemv"),
-                     "kernel": "mglu::stream_resident_kernel<mglu::Bf16Traits, 4, 0, 2>",
+                     "kernel": "mglu::stream_resident_kernel<mglu::Bf16Traits, 4, 0, 2, true>",
                      "bytes_per_launch": head.bytes},
     }
     if not args.no_refs:
