@@ -317,6 +317,14 @@ __device__ __forceinline__ void route_weights(const EpilogueParams &e, long tok,
     }
 }
 
+// One mask's term of Eq. 3 from the reduced sums t and dsum_i (before any route weight).
+__device__ __forceinline__ float mglu_term(const EpilogueParams &e, float t, float dsum)
+{
+    const float gate = (e.mask_use & 1) ? t : gate_of(t, dsum);
+    const float value = (e.mask_use & 2) ? t : value_of(t, dsum);
+    return gate_fn_apply(e.gate_fn, gate) * value;
+}
+
 // One output element of the layer from its reduced sums: t and dsum[0 .. n_masks).
 template <int NMP>
 __device__ __forceinline__ float mglu_mix(const EpilogueParams &e, const float (&rw)[NMP], float t,
@@ -326,9 +334,7 @@ __device__ __forceinline__ float mglu_mix(const EpilogueParams &e, const float (
 #pragma unroll
     for (int i = 0; i < NMP; ++i) {
         if (i >= e.n_masks) break;
-        const float gate = (e.mask_use & 1) ? t : gate_of(t, dsum[i]);
-        const float value = (e.mask_use & 2) ? t : value_of(t, dsum[i]);
-        const float term = gate_fn_apply(e.gate_fn, gate) * value;
+        const float term = mglu_term(e, t, dsum[i]);
         sum += e.route ? rw[i] * term : term;
     }
     return sum;

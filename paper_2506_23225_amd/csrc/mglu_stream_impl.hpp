@@ -163,6 +163,19 @@ __device__ __forceinline__ EpilogueParams epilogue_params(const StreamParams &p)
                                     : EpilogueParams{p.n_masks, 0, 0, nullptr};
 }
 
+// Four consecutive outputs of one token, rounded once to the output type; the last columns of a ragged d_ff one by one.
+template <typename Tr>
+__device__ __forceinline__ void store_out4(const StreamParams &p, f32x4 y, long o, int j0, bool full)
+{
+    if (full) {
+        Tr::store4(p.out, o, y);
+    } else {
+#pragma unroll
+        for (int c = 0; c < 4; ++c)
+            if (j0 + c < p.d) Tr::store1(p.out, o + c, y[c]);
+    }
+}
+
 // rw: the route weights of this lane's token of every token block (see route_weights).
 template <typename Tr, int NMP, int TB, int MODE>
 __device__ __forceinline__ void epilogue(const StreamParams &p, const f32x4 (&acc)[sets_of(MODE, NMP)][TB],
@@ -207,13 +220,7 @@ __device__ __forceinline__ void epilogue(const StreamParams &p, const f32x4 (&ac
                     y[c] = mglu_mix<NMP>(ep, rw[tb], acc[0][tb][c], ds);
                 }
             }
-            if (full) {
-                Tr::store4(p.out, o, y);
-            } else {
-#pragma unroll
-                for (int c = 0; c < 4; ++c)
-                    if (j0 + c < p.d) Tr::store1(p.out, o + c, y[c]);
-            }
+            store_out4<Tr>(p, y, o, j0, full);
         }
     }
 }
@@ -303,6 +310,14 @@ __attribute__((amdgpu_waves_per_eu(resident_min_waves(Tr::ELEM_BYTES, MODE, NMP)
         p.n_masks = n_act;  // what the epilogue sums over
     } else {
         route_weights<NMP>(epilogue_params<MODE>(p), tok0 + r, false, rw[0]);
+    }
+    // the weights of the masks this wavefront finishes in the shared epilogue: (compact) index wave + a * nw
+    float rw_mine[NMP];
+#pragma unroll
+    for (int a = 0; a < NMP; ++a) {
+        rw_mine[a] = rw[0][0];
+#pragma unroll
+        for (int i = 1; i < NMP; ++i) rw_mine[a] = (wave + a * nw == i) ? rw[0][i] : rw_mine[a];
     }
 
     auto load_chunk = [&](chunk_t &c, int kc) __attribute__((always_inline)) {
@@ -399,21 +414,66 @@ __attribute__((amdgpu_waves_per_eu(resident_min_waves(Tr::ELEM_BYTES, MODE, NMP)
         compute(buf[s], kc_of(i0 + R + s));
     }
 
-    // ---- combine the K split: wavefronts 1..nw-1 hand their sums to wavefront 0 through LDS,
-    //      which adds them in wavefront order (fixed order => reproducible bits) ----
-    if (nw > 1) {
-        if (wave > 0 && r < tc) {
+    // ---- combine the K split and finish.  Sums are always added in wavefront order (fixed order =>
+    //      reproducible bits). ----
+    if constexpr (MODE == kModeMglu || MODE == kModeMgluVariant) {
+        if (nw > 1) {
+            // Eq. 3 costs a few hundred instructions per lane (an exp, a reciprocal per column and
+            // mask), which one wavefront at the end of every workgroup would run alone: every
+            // wavefront publishes its sums, then wavefront w finishes the masks w, w + nw, ... and
+            // wavefront 0 adds the shares.
+            f32x4 *lds_term = lds_red + nw * SETS * 4 * tc;
+            const int slot = q * tc + r;
+            if (r < tc) {
 #pragma unroll
-            for (int s = 0; s < SETS; ++s) lds_red[((wave - 1) * SETS + s) * (4 * tc) + q * tc + r] = acc[s][0];
-        }
-        __syncthreads();
-        if (wave == 0 && r < tc) {
-            for (int w = 1; w < nw; ++w)
+                for (int s = 0; s < SETS; ++s) lds_red[(wave * SETS + s) * (4 * tc) + slot] = acc[s][0];
+            }
+            __syncthreads();
+            if (r < tc) {
+                const EpilogueParams ep = epilogue_params<MODE>(p);
+                f32x4 t = lds_red[slot];
+                for (int w = 1; w < nw; ++w) t += lds_red[(w * SETS) * (4 * tc) + slot];
+                f32x4 share = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-                for (int s = 0; s < SETS; ++s) acc[s][0] += lds_red[((w - 1) * SETS + s) * (4 * tc) + q * tc + r];
+                for (int a = 0; a < NMP; ++a) {
+                    const int i = wave + a * nw;
+                    if (i >= p.n_masks) break;  // uniform over the wavefront
+                    f32x4 ds = lds_red[(1 + i) * (4 * tc) + slot];
+                    for (int w = 1; w < nw; ++w) ds += lds_red[(w * SETS + 1 + i) * (4 * tc) + slot];
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) {
+                        const float term = mglu_term(ep, t[c], ds[c]);
+                        share[c] += ep.route ? rw_mine[a] * term : term;
+                    }
+                }
+                lds_term[wave * (4 * tc) + slot] = share;
+            }
+            __syncthreads();
+            const int j0 = jb * kColBlock + 4 * q;
+            if (wave == 0 && r < tc && j0 < p.d) {
+                f32x4 y = lds_term[slot];
+                for (int w = 1; w < nw; ++w) y += lds_term[w * (4 * tc) + slot];
+                store_out4<Tr>(p, y, (long)(tok0 + r) * p.d + j0, j0, (j0 + 3 < p.d) && ((p.d & 3) == 0));
+            }
+        } else {
+            epilogue<Tr, NMP, 1, MODE>(p, acc, rw, jb, tok0, r, q);
         }
+    } else {
+        // wavefronts 1..nw-1 hand their sums to wavefront 0 through LDS
+        if (nw > 1) {
+            if (wave > 0 && r < tc) {
+#pragma unroll
+                for (int s = 0; s < SETS; ++s) lds_red[((wave - 1) * SETS + s) * (4 * tc) + q * tc + r] = acc[s][0];
+            }
+            __syncthreads();
+            if (wave == 0 && r < tc) {
+                for (int w = 1; w < nw; ++w)
+#pragma unroll
+                    for (int s = 0; s < SETS; ++s) acc[s][0] += lds_red[((w - 1) * SETS + s) * (4 * tc) + q * tc + r];
+            }
+        }
+        if (wave == 0) epilogue<Tr, NMP, 1, MODE>(p, acc, rw, jb, tok0, r, q);
     }
-    if (wave == 0) epilogue<Tr, NMP, 1, MODE>(p, acc, rw, jb, tok0, r, q);
 }
 
 // ================================================================================================
@@ -607,7 +667,8 @@ static StreamPlan plan_stream(const StreamParams &p, int elem_kind, int nmp, int
     int nw_shift = 0;
     while ((2 << nw_shift) <= MGLU_STREAM_MAX_WAVES && (4 << nw_shift) <= p.NC) ++nw_shift;
     const int nw = 1 << nw_shift;
-    const size_t red = nw > 1 ? (size_t)(nw - 1) * sets * 4 * tc * sizeof(f32x4) : 0;
+    // hand-over area: every wavefront's sums plus, for the shared epilogue, every wavefront's share
+    const size_t red = nw > 1 ? (size_t)(nw * sets + nw) * 4 * tc * sizeof(f32x4) : 0;
     const size_t xb = (size_t)resident_x_frags_padded((p.NC * tiles * 4) << resident_row_shift(tc), nw_shift) * 16;
     if (p.T <= MGLU_RESIDENT_MAX_T && xb + red <= kLdsBudget) {
         pl.resident = true;
