@@ -277,14 +277,14 @@ def extra_cases(synth):
                           synth.config("large", n_masks=n_m, tokens=T), "hbm", 60, 6))
     # the paper's own precision on the shape of its kernel timings (4096 x 14336, 4 masks, batch 1), and its prefill twin
     cases.append(("fp16 4096x14336 n_m=4 T=1", synth.config("prefill_8b", tokens=1, dtype="f16"), "hbm", 200, 20))
-    cases.append(("prefill_8b 4096x14336 n_m=4 T=4096", synth.config("prefill_8b"), "mfma", 10, 2))
-    cases.append(("fp16 4096x14336 n_m=4 T=4096", synth.config("prefill_8b", dtype="f16"), "mfma", 10, 2))
+    cases.append(("prefill_8b 4096x14336 n_m=4 T=4096", synth.config("prefill_8b"), "mfma", 20, 20))
+    cases.append(("fp16 4096x14336 n_m=4 T=4096", synth.config("prefill_8b", dtype="f16"), "mfma", 20, 20))
     # 16 masks, the paper's largest ablation
     cases.append(("decode_8b 4096x14336 n_m=16 T=1", synth.config("decode_8b", n_masks=16, tokens=1), "hbm", 100, 10))
-    cases.append(("prefill_8b 4096x14336 n_m=16 T=4096", synth.config("prefill_8b", n_masks=16), "mfma", 5, 1))
+    cases.append(("prefill_8b 4096x14336 n_m=16 T=4096", synth.config("prefill_8b", n_masks=16), "mfma", 8, 8))
     for n_m in (1, 2, 4, 8):
         cases.append(("large 8192x28672 n_m=%d T=2048" % n_m,
-                      synth.config("large", n_masks=n_m, tokens=2048), "mfma", 5, 1))
+                      synth.config("large", n_masks=n_m, tokens=2048), "mfma", 10, 10))
     return cases
 
 
@@ -345,7 +345,7 @@ def run_widened(torch, synth, only):
     cases = [("routed top-2 of 8, decode_8b 4096x14336 T=1", synth.config("decode_8b", tokens=1), "routed", 200, 20),
              ("routed top-2 of 8, large 8192x28672 T=1", synth.config("large", n_masks=8, tokens=1), "routed", 60, 6),
              ("ffn (layer + output projection), decode_8b 4096x14336 n_m=8 T=1", synth.config("decode_8b", tokens=1), "ffn", 200, 20),
-             ("ffn (layer + output projection), prefill_8b 4096x14336 n_m=4 T=4096", synth.config("prefill_8b"), "ffn", 10, 2)]
+             ("ffn (layer + output projection), prefill_8b 4096x14336 n_m=4 T=4096", synth.config("prefill_8b"), "ffn", 20, 20)]
     for name, cfg, kind, steps, warmup in cases:
         if only and not any(o in name for o in only):
             continue
