@@ -28,8 +28,8 @@ HEADLINE = "decode_gemv 2048x5632 n_m=4 T=1"
 def parse_args():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=2000)
-    ap.add_argument("--warmup", type=int, default=200)
+    ap.add_argument("--steps", type=int, default=5000)
+    ap.add_argument("--warmup", type=int, default=1000)
     ap.add_argument("--no-extra", action="store_true", help="headline workload only")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     ap.add_argument("--no-refs", action="store_true",
@@ -270,17 +270,17 @@ def measured_traffic(key):
 def extra_cases(synth):
     cases = []
     for T in (1, 4, 16):
-        cases.append(("decode_8b 4096x14336 n_m=8 T=%d" % T, synth.config("decode_8b", tokens=T), "hbm", 200, 20))
+        cases.append(("decode_8b 4096x14336 n_m=8 T=%d" % T, synth.config("decode_8b", tokens=T), "hbm", 400, 200))
     for n_m in (1, 2, 4, 8):
         for T in (1, 32):
             cases.append(("large 8192x28672 n_m=%d T=%d" % (n_m, T),
-                          synth.config("large", n_masks=n_m, tokens=T), "hbm", 60, 6))
+                          synth.config("large", n_masks=n_m, tokens=T), "hbm", 100, 60))
     # the paper's own precision on the shape of its kernel timings (4096 x 14336, 4 masks, batch 1), and its prefill twin
-    cases.append(("fp16 4096x14336 n_m=4 T=1", synth.config("prefill_8b", tokens=1, dtype="f16"), "hbm", 200, 20))
+    cases.append(("fp16 4096x14336 n_m=4 T=1", synth.config("prefill_8b", tokens=1, dtype="f16"), "hbm", 400, 200))
     cases.append(("prefill_8b 4096x14336 n_m=4 T=4096", synth.config("prefill_8b"), "mfma", 20, 20))
     cases.append(("fp16 4096x14336 n_m=4 T=4096", synth.config("prefill_8b", dtype="f16"), "mfma", 20, 20))
     # 16 masks, the paper's largest ablation
-    cases.append(("decode_8b 4096x14336 n_m=16 T=1", synth.config("decode_8b", n_masks=16, tokens=1), "hbm", 100, 10))
+    cases.append(("decode_8b 4096x14336 n_m=16 T=1", synth.config("decode_8b", n_masks=16, tokens=1), "hbm", 300, 150))
     cases.append(("prefill_8b 4096x14336 n_m=16 T=4096", synth.config("prefill_8b", n_masks=16), "mfma", 8, 8))
     for n_m in (1, 2, 4, 8):
         cases.append(("large 8192x28672 n_m=%d T=2048" % n_m,
@@ -342,9 +342,9 @@ def run_extras(torch, synth, args):
 def run_widened(torch, synth, only):
     """Rows beyond the up-projection itself: the Top-K routed layer and the whole FFN block."""
     out = []
-    cases = [("routed top-2 of 8, decode_8b 4096x14336 T=1", synth.config("decode_8b", tokens=1), "routed", 200, 20),
-             ("routed top-2 of 8, large 8192x28672 T=1", synth.config("large", n_masks=8, tokens=1), "routed", 60, 6),
-             ("ffn (layer + output projection), decode_8b 4096x14336 n_m=8 T=1", synth.config("decode_8b", tokens=1), "ffn", 200, 20),
+    cases = [("routed top-2 of 8, decode_8b 4096x14336 T=1", synth.config("decode_8b", tokens=1), "routed", 400, 200),
+             ("routed top-2 of 8, large 8192x28672 T=1", synth.config("large", n_masks=8, tokens=1), "routed", 100, 60),
+             ("ffn (layer + output projection), decode_8b 4096x14336 n_m=8 T=1", synth.config("decode_8b", tokens=1), "ffn", 400, 200),
              ("ffn (layer + output projection), prefill_8b 4096x14336 n_m=4 T=4096", synth.config("prefill_8b"), "ffn", 20, 20)]
     for name, cfg, kind, steps, warmup in cases:
         if only and not any(o in name for o in only):
