@@ -46,6 +46,14 @@ namespace mglu {
 #define MGLU_PREFILL_WAVES 8   // wavefronts per workgroup (8: one workgroup per CU; 4: two)
 #endif
 constexpr int kPrefillWaves = MGLU_PREFILL_WAVES;
+// LDS buffers of one chunk of x each.  2: a chunk is staged while the one before it is multiplied, one
+// barrier per chunk.  4: staged two chunks ahead, one barrier per two chunks, so that the wavefronts
+// of a workgroup may drift a chunk apart instead of meeting after every chunk.
+#ifndef MGLU_PREFILL_XBUF
+#define MGLU_PREFILL_XBUF 2
+#endif
+constexpr int kPrefillXBuf = MGLU_PREFILL_XBUF;
+constexpr int kPrefillXAhead = kPrefillXBuf / 2;   // chunks between staging and use
 
 // AD: how many tiles ahead of the multiply the A fragments are fetched.
 template <typename Tr, int NMP, int CB, int TB, int MODE, int AD>
@@ -175,25 +183,30 @@ void prefill_kernel(PrefillParams p)
         }
     };
 
-    // ---- prologue: stage chunk 0 of x, start the A ring and the masks ----
+    // ---- prologue: stage the first chunk(s) of x, start the A ring and the masks ----
     const int last = p.NC - 1;
     {
-        frag xv[XPIECES];
+        frag xv[kPrefillXAhead][XPIECES];
 #pragma unroll
-        for (int s = 0; s < XPIECES; ++s) xv[s] = *x_src(0, s);
+        for (int c = 0; c < kPrefillXAhead; ++c)
+#pragma unroll
+            for (int s = 0; s < XPIECES; ++s) xv[c][s] = *x_src(min(c, last), s);
         load_masks(0, 0);
 #pragma unroll
         for (int t = 0; t < AD; ++t) load_a(0, t, t);
 #pragma unroll
-        for (int s = 0; s < XPIECES; ++s) *x_dst(0, s) = xv[s];
+        for (int c = 0; c < kPrefillXAhead; ++c)
+#pragma unroll
+            for (int s = 0; s < XPIECES; ++s) *x_dst(c, s) = xv[c][s];
     }
     __syncthreads();
 
     // One chunk of the K loop; MS = which half of mk[] holds this chunk's masks (compile time).
     auto chunk_step = [&](int kc, auto ms_tag) __attribute__((always_inline)) {
         constexpr int MS = decltype(ms_tag)::value;
-        const int buf = kc & 1;
+        const int buf = kc & (kPrefillXBuf - 1);
         const int kn = min(kc + 1, last);   // next chunk, clamped: its loads are then always in bounds
+        const int kx = min(kc + kPrefillXAhead, last);   // the chunk of x staged during this one
         frag xv[XPIECES];
         // B fragments are read from LDS one pair of token blocks ahead of the MFMAs that use them
         // (the compiler, left alone, issues each read right before its use and eats the LDS latency
@@ -219,7 +232,7 @@ void prefill_kernel(PrefillParams p)
             // first use, which would expose the whole memory latency.
 #pragma unroll
             for (int s = 0; s < XPIECES; ++s)
-                if (MGLU_PREFILL_XLOAD_TILE(s, XPIECES) == t) xv[s] = *x_src(kn, s);
+                if (MGLU_PREFILL_XLOAD_TILE(s, XPIECES) == t) xv[s] = *x_src(kx, s);
             if (t + AD < 4) load_a(kc, t + AD, (t + AD) % AR);
             else load_a(kn, t + AD - 4, (t + AD) % AR);
             if (t == 0) load_masks(kn, MS ^ 1);
@@ -285,9 +298,13 @@ void prefill_kernel(PrefillParams p)
             }
 #pragma unroll
             for (int s = 0; s < XPIECES; ++s)   // a piece is stored one tile after its load was issued
-                if (MGLU_PREFILL_XSTORE_TILE(s, XPIECES) == t) *x_dst(buf ^ 1, s) = xv[s];
+                if (MGLU_PREFILL_XSTORE_TILE(s, XPIECES) == t)
+                    *x_dst((kc + kPrefillXAhead) & (kPrefillXBuf - 1), s) = xv[s];
         }
-        __syncthreads();
+        // with two buffers every chunk ends in a barrier; with four only every second one (a buffer
+        // is written two chunks after its last read and read two chunks after it was written, and
+        // one barrier lies in between either way)
+        if (kPrefillXBuf == 2 || MS == 1) __syncthreads();
     };
 
     int kc = 0;
@@ -352,8 +369,13 @@ static hipError_t launch_prefill_one(PrefillParams p, hipStream_t stream)
     // every XCD gets per_xcd column tiles x tiles_m token tiles; ids beyond a band's end return at once
     const int per_xcd = (p.tiles_n + 7) / 8;
     const long wgs = (long)8 * per_xcd * p.tiles_m;
-    const size_t lds = (size_t)2 * 4 * TB * kWave * sizeof(f32x4);
+    const size_t lds = (size_t)kPrefillXBuf * 4 * TB * kWave * sizeof(f32x4);
     auto kern = prefill_kernel<Tr, NMP, CB, TB, MODE, AD>;
+    if (lds > 64 * 1024) {   // beyond the default dynamic LDS limit: allowed once per kernel
+        static hipError_t allowed = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                                        hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        if (allowed != hipSuccess) return allowed;
+    }
     hipLaunchKernelGGL(kern, dim3((unsigned)wgs), dim3(kPrefillWaves * kWave), lds, stream, p);
     return hipGetLastError();
 }
