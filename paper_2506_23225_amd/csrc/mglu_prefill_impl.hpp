@@ -326,9 +326,11 @@ void prefill_kernel(PrefillParams p)
         for (int tb = 0; tb < TB; ++tb) {
             const long tok = (long)tok0 + 16 * tb + r;
             if (tok >= p.T) continue;
+            // plain mode: all NMP masks, a compile-time bound (a padding mask is all-value: its sum
+            // equals t bit for bit, its gate is 0 and its term exactly 0)
             const EpilogueParams ep = MODE == kModeMgluVariant
                                           ? EpilogueParams{p.n_masks, p.gate_fn, p.mask_use, p.route}
-                                          : EpilogueParams{p.n_masks, 0, 0, nullptr};
+                                          : EpilogueParams{NMP, 0, 0, nullptr};
             float rw[NMP];
             route_weights<NMP>(ep, tok, true, rw);
             f32x4 y;
@@ -342,7 +344,7 @@ void prefill_kernel(PrefillParams p)
                     float ds[NMP];
 #pragma unroll
                     for (int i = 0; i < NMP; ++i) ds[i] = acc[1 + i][cb][tb][c];
-                    y[c] = mglu_mix<NMP>(ep, rw, acc[0][cb][tb][c], ds);
+                    y[c] = mglu_mix<NMP, MODE == kModeMglu>(ep, rw, acc[0][cb][tb][c], ds);
                 }
             }
             const long o = tok * p.d + j0;

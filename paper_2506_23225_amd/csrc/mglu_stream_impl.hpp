@@ -156,11 +156,14 @@ __device__ __forceinline__ void mma_tile(f32x4 (&acc)[sets_of(MODE, NMP)][TB], c
 }
 
 // Epilogue on the reduced sums (Eq. 3): lane (r, q) holds token 16 tb + r, columns 4q .. 4q+3 of block jb.
-template <int MODE>
+// In the plain mode the mask count is the padded one, a compile-time constant: a padding mask is
+// all-value (its packed words are zero), so its sum equals t bit for bit, its gate is exactly 0 and
+// its term swish(0) * value = 0 -- computing it costs less than a run-time bound on every element.
+template <int MODE, int NMP>
 __device__ __forceinline__ EpilogueParams epilogue_params(const StreamParams &p)
 {
     return MODE == kModeMgluVariant ? EpilogueParams{p.n_masks, p.gate_fn, p.mask_use, p.route}
-                                    : EpilogueParams{p.n_masks, 0, 0, nullptr};
+                                    : EpilogueParams{NMP, 0, 0, nullptr};
 }
 
 // Four consecutive outputs of one token, rounded once to the output type; the last columns of a ragged d_ff one by one.
@@ -205,7 +208,7 @@ __device__ __forceinline__ void epilogue(const StreamParams &p, const f32x4 (&ac
                 }
             }
         } else {
-            const EpilogueParams ep = epilogue_params<MODE>(p);
+            const EpilogueParams ep = epilogue_params<MODE, NMP>(p);
             f32x4 y;
 #pragma unroll
             for (int c = 0; c < 4; ++c) {
@@ -217,7 +220,7 @@ __device__ __forceinline__ void epilogue(const StreamParams &p, const f32x4 (&ac
                     float ds[NMP];
 #pragma unroll
                     for (int i = 0; i < NMP; ++i) ds[i] = acc[1 + i][tb][c];
-                    y[c] = mglu_mix<NMP>(ep, rw[tb], acc[0][tb][c], ds);
+                    y[c] = mglu_mix<NMP, MODE == kModeMglu>(ep, rw[tb], acc[0][tb][c], ds);
                 }
             }
             store_out4<Tr>(p, y, o, j0, full);
@@ -293,7 +296,7 @@ __attribute__((amdgpu_waves_per_eu(resident_min_waves(Tr::ELEM_BYTES, MODE, NMP)
     for (int i = 0; i < NMP; ++i) idx[i] = i;
     if constexpr (MODE == kModeMgluVariant) {
         float w_all[NMP];
-        route_weights<NMP>(epilogue_params<MODE>(p), tok0 + r, r < tc, w_all);
+        route_weights<NMP>(epilogue_params<MODE, NMP>(p), tok0 + r, r < tc, w_all);
         uint32_t active = 0u;
 #pragma unroll
         for (int i = 0; i < NMP; ++i)
@@ -309,7 +312,7 @@ __attribute__((amdgpu_waves_per_eu(resident_min_waves(Tr::ELEM_BYTES, MODE, NMP)
         }
         p.n_masks = n_act;  // what the epilogue sums over
     } else {
-        route_weights<NMP>(epilogue_params<MODE>(p), tok0 + r, false, rw[0]);
+        route_weights<NMP>(epilogue_params<MODE, NMP>(p), tok0 + r, false, rw[0]);
     }
     // the weights of the masks this wavefront finishes in the shared epilogue: (compact) index wave + a * nw
     float rw_mine[NMP];
@@ -430,7 +433,7 @@ __attribute__((amdgpu_waves_per_eu(resident_min_waves(Tr::ELEM_BYTES, MODE, NMP)
             }
             __syncthreads();
             if (r < tc) {
-                const EpilogueParams ep = epilogue_params<MODE>(p);
+                const EpilogueParams ep = epilogue_params<MODE, NMP>(p);
                 f32x4 t = lds_red[slot];
                 for (int w = 1; w < nw; ++w) t += lds_red[(w * SETS) * (4 * tc) + slot];
                 f32x4 share = {0.f, 0.f, 0.f, 0.f};
@@ -631,7 +634,7 @@ void stream_panel_kernel(StreamParams p)
         float rw[TB][NMP];
 #pragma unroll
         for (int tb = 0; tb < TB; ++tb)
-            route_weights<NMP>(epilogue_params<MODE>(p), tok0 + 16 * tb + r, tok0 + 16 * tb + r < p.T, rw[tb]);
+            route_weights<NMP>(epilogue_params<MODE, NMP>(p), tok0 + 16 * tb + r, tok0 + 16 * tb + r < p.T, rw[tb]);
         epilogue<Tr, NMP, TB, MODE>(p, acc, rw, jb, tok0, r, q);
     }
 }
