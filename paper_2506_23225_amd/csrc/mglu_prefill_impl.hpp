@@ -15,7 +15,8 @@
 //   A operand (W): streamed straight from global memory in the packed tile order -- each
 //     wavefront reads only its own column blocks, so LDS staging would buy no reuse
 //   masks: read next to W, one chunk (128 k) of words at a time, applied in registers
-//   B operand (x): shared by all 8 wavefronts -> staged through LDS in B-fragment order,
+//   B operand (x): shared by all 8 wavefronts -> staged through LDS in B-fragment order by loads
+//     that go from global memory straight to LDS (no registers, no LDS write instructions),
 //     double-buffered per 128-k chunk, one barrier per chunk
 //   MFMA: v_mfma_f32_16x16x32_bf16, 16 columns x 16 tokens per accumulator
 // Workgroup ids are remapped so that the workgroups resident on one XCD (ids equal mod 8)
@@ -40,7 +41,6 @@ namespace mglu {
 // In which tile of a chunk the s-th x piece of the next chunk is loaded / written to LDS.
 #ifndef MGLU_PREFILL_XLOAD_TILE
 #define MGLU_PREFILL_XLOAD_TILE(s, n) ((s) * 3 / (n))
-#define MGLU_PREFILL_XSTORE_TILE(s, n) ((s) * 3 / (n) + 1)
 #endif
 #ifndef MGLU_PREFILL_WAVES
 #define MGLU_PREFILL_WAVES 8   // wavefronts per workgroup (8: one workgroup per CU; 4: two)
@@ -53,6 +53,10 @@ constexpr int kPrefillWaves = MGLU_PREFILL_WAVES;
 #define MGLU_PREFILL_XBUF 2
 #endif
 constexpr int kPrefillXBuf = MGLU_PREFILL_XBUF;
+#ifndef MGLU_PREFILL_MASK_MAJOR
+#define MGLU_PREFILL_MASK_MAJOR 1
+#endif
+constexpr bool kPrefillMaskMajor = MGLU_PREFILL_MASK_MAJOR;
 constexpr int kPrefillXAhead = kPrefillXBuf / 2;   // chunks between staging and use
 
 // AD: how many tiles ahead of the multiply the A fragments are fetched.
@@ -131,15 +135,19 @@ void prefill_kernel(PrefillParams p)
         const int tb = (wave + kPrefillWaves * s) >> 2;
         xrow[s] = (uint32_t)(min(tok0 + 16 * tb + r, p.T - 1) - tok0) * (uint32_t)(p.h * 2);
     }
-    auto x_src = [&](int kc, int s) __attribute__((always_inline)) {
-        const int t = (wave + kPrefillWaves * s) & 3;
-        const uint32_t kb = min((uint32_t)(kc * kChunkK + 32 * t) * 2 + q * 16, klim);
-        return reinterpret_cast<const frag *>(xbase + (xrow[s] + kb));
-    };
-    auto x_dst = [&](int buf, int s) __attribute__((always_inline)) {
+    // One fragment of x goes from global memory straight to LDS (no registers in between): the load
+    // takes a per-lane byte offset into a buffer and a wavefront-uniform LDS address, and lane l's 16
+    // bytes land at that address + 16 l -- exactly a B fragment's slot order.  The buffer is this
+    // workgroup's token rows (offsets past its end would read as zero; the clamps keep them inside).
+    const __amdgpu_buffer_rsrc_t xrsrc = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<char *>(xbase), 0, (min(tok0 + 16 * TB, p.T) - tok0) * p.h * 2, 0x00020000);
+    auto stage_x = [&](int kc, int buf, int s) __attribute__((always_inline)) {
         const int idx = wave + kPrefillWaves * s;
         const int tb = idx >> 2, t = idx & 3;
-        return lds_x + ((buf * 4 + t) * TB + tb) * kWave + lane;
+        const uint32_t kb = min((uint32_t)(kc * kChunkK + 32 * t) * 2 + q * 16, klim);
+        frag *dst = lds_x + ((buf * 4 + t) * TB + tb) * kWave;   // uniform over the wavefront
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(xrsrc, (__attribute__((address_space(3))) void *)dst, 16,
+                                                 (int)(xrow[s] + kb), 0, 0, 0);
     };
 
     // ---- A ring: entry t holds the fragments of tile t of the current (or next) chunk ----
@@ -183,23 +191,28 @@ void prefill_kernel(PrefillParams p)
         }
     };
 
+    constexpr int A_LOADS = CB * (MODE == kModeSwiglu ? 2 : 1);   // load instructions of one load_a / load_masks
+    constexpr int M_LOADS = (MODE == kModeSwiglu || MODE == kModeLinear) ? 0 : CB * (NMP >= 8 ? NMP / 4 : 1);
+    auto wait_vm = [](auto n) __attribute__((always_inline)) {
+        asm volatile("s_waitcnt vmcnt(%0)" ::"n"(decltype(n)::value) : "memory");
+    };
+
     // ---- prologue: stage the first chunk(s) of x, start the A ring and the masks ----
     const int last = p.NC - 1;
     {
-        frag xv[kPrefillXAhead][XPIECES];
 #pragma unroll
         for (int c = 0; c < kPrefillXAhead; ++c)
 #pragma unroll
-            for (int s = 0; s < XPIECES; ++s) xv[c][s] = *x_src(min(c, last), s);
+            for (int s = 0; s < XPIECES; ++s) stage_x(min(c, last), c, s);
+        __builtin_amdgcn_sched_barrier(0);   // the x loads stay the oldest ones in flight
         load_masks(0, 0);
 #pragma unroll
         for (int t = 0; t < AD; ++t) load_a(0, t, t);
-#pragma unroll
-        for (int c = 0; c < kPrefillXAhead; ++c)
-#pragma unroll
-            for (int s = 0; s < XPIECES; ++s) *x_dst(c, s) = xv[c][s];
     }
-    __syncthreads();
+    // Loads complete in issue order, so "at most the loads issued after them outstanding" means the x
+    // fragments are in LDS; the compiler does not know that the hand-placed LDS reads depend on them.
+    wait_vm(std::integral_constant<int, M_LOADS + AD * A_LOADS>{});
+    __builtin_amdgcn_s_barrier();
 
     // One chunk of the K loop; MS = which half of mk[] holds this chunk's masks (compile time).
     auto chunk_step = [&](int kc, auto ms_tag) __attribute__((always_inline)) {
@@ -207,7 +220,6 @@ void prefill_kernel(PrefillParams p)
         const int buf = kc & (kPrefillXBuf - 1);
         const int kn = min(kc + 1, last);   // next chunk, clamped: its loads are then always in bounds
         const int kx = min(kc + kPrefillXAhead, last);   // the chunk of x staged during this one
-        frag xv[XPIECES];
         // B fragments are read from LDS one pair of token blocks ahead of the MFMAs that use them
         // (the compiler, left alone, issues each read right before its use and eats the LDS latency
         // three times per tile).  The first pair of a chunk cannot be fetched before the barrier.
@@ -222,8 +234,24 @@ void prefill_kernel(PrefillParams p)
             asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(b[0]) : "v"(xchunk), "n"((t * TB + 2 * pi) * 1024));
             asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(b[1]) : "v"(xchunk), "n"((t * TB + 2 * pi + 1) * 1024));
         };
+        // Mask-major tiles (four masks): all B fragments of a tile stay in registers, one set per tile
+        // parity, and the sets are multiplied one after the other -- so mask i + 1's operand is prepared
+        // in the issue slots between the MFMAs of mask i instead of ahead of the whole tile.  Worth
+        // about 1 % there; with eight masks the second set of B fragments no longer fits the registers.
+        constexpr bool MASK_MAJOR = kPrefillMaskMajor && TB == 6 && MODE != kModeSwiglu && MODE != kModeLinear;
+        auto read_tile = [&](frag (&b)[TB], int t) __attribute__((always_inline)) {
+#pragma unroll
+            for (int tb = 0; tb < TB; ++tb)
+                asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(b[tb]) : "v"(xchunk), "n"((t * TB + tb) * 1024));
+        };
+        // wait until at most `newer` LDS operations issued after fragment b are outstanding, then release b
+        auto wait_frag = [&](frag &b, int newer) __attribute__((always_inline)) {
+            asm volatile("s_waitcnt lgkmcnt(%1)" : "+v"(b) : "n"(newer));
+        };
+        frag btile[MASK_MAJOR ? 2 : 1][TB];
         frag bcur[2], bnxt[2];
-        read_pair(bcur, 0, 0);
+        if constexpr (MASK_MAJOR) read_tile(btile[0], 0);
+        else read_pair(bcur, 0, 0);
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
             // Issue this tile's prefetches first: pieces of the next chunk's x (stored one tile
@@ -232,13 +260,68 @@ void prefill_kernel(PrefillParams p)
             // first use, which would expose the whole memory latency.
 #pragma unroll
             for (int s = 0; s < XPIECES; ++s)
-                if (MGLU_PREFILL_XLOAD_TILE(s, XPIECES) == t) xv[s] = *x_src(kx, s);
+                if (MGLU_PREFILL_XLOAD_TILE(s, XPIECES) == t)
+                    stage_x(kx, (kc + kPrefillXAhead) & (kPrefillXBuf - 1), s);
+            __builtin_amdgcn_sched_barrier(0);   // x first: the wait at the end of the chunk counts on it
             if (t + AD < 4) load_a(kc, t + AD, (t + AD) % AR);
             else load_a(kn, t + AD - 4, (t + AD) % AR);
             if (t == 0) load_masks(kn, MS ^ 1);
             __builtin_amdgcn_sched_barrier(0);
 
-            if constexpr (TB == 2 && MODE != kModeSwiglu && MODE != kModeLinear) {
+            if constexpr (MASK_MAJOR) {
+                frag (&b)[TB] = btile[t & 1];
+                frag var[2][CB];
+                constexpr int PER_SET = TB * CB;             // MFMAs of one set
+                constexpr int FLIP_VALU = 6 * CB;            // vector instructions of one mask's operand
+                constexpr int PER_GAP = (FLIP_VALU + PER_SET - 1) / PER_SET;
+                // issue order of one set: its MFMAs one by one, the next operand's instructions in the gaps
+                auto interleave = [&](bool with_flip) __attribute__((always_inline)) {
+                    int left = with_flip ? FLIP_VALU : 0;
+#pragma unroll
+                    for (int k = 0; k < PER_SET; ++k) {
+                        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                        if (left >= 2 && PER_GAP >= 2) __builtin_amdgcn_sched_group_barrier(0x002, 2, 0);
+                        else if (left >= 1) __builtin_amdgcn_sched_group_barrier(0x002, 1, 0);
+                        left -= left >= PER_GAP ? PER_GAP : left;
+                    }
+                };
+#pragma unroll
+                for (int cb = 0; cb < CB; ++cb) var[0][cb] = Tr::template flip<NMP>(aw[t][cb], mk[MS][cb], t, 0);
+                if (t == 0) {
+                    // this tile's reads were issued right after the barrier: take the fragments as they land
+#pragma unroll
+                    for (int tb = 0; tb < TB; ++tb) {
+                        wait_frag(b[tb], TB - 1 - tb);
+#pragma unroll
+                        for (int cb = 0; cb < CB; ++cb) acc[0][cb][tb] = Tr::mma(aw[t][cb], b[tb], acc[0][cb][tb]);
+                    }
+                    read_tile(btile[1], 1);
+                } else {
+                    // read the next tile's fragments now; this tile's were issued a tile ago
+                    if (t + 1 < 4) read_tile(btile[(t + 1) & 1], t + 1);
+#pragma unroll
+                    for (int tb = 0; tb < TB; ++tb) wait_frag(b[tb], t + 1 < 4 ? TB : 0);
+#pragma unroll
+                    for (int tb = 0; tb < TB; ++tb)
+#pragma unroll
+                        for (int cb = 0; cb < CB; ++cb) acc[0][cb][tb] = Tr::mma(aw[t][cb], b[tb], acc[0][cb][tb]);
+                }
+                interleave(true);
+#pragma unroll
+                for (int i = 0; i < NMP; ++i) {
+                    if (i + 1 < NMP) {
+#pragma unroll
+                        for (int cb = 0; cb < CB; ++cb)
+                            var[(i + 1) & 1][cb] = Tr::template flip<NMP>(aw[t][cb], mk[MS][cb], t, i + 1);
+                    }
+#pragma unroll
+                    for (int tb = 0; tb < TB; ++tb)
+#pragma unroll
+                        for (int cb = 0; cb < CB; ++cb)
+                            acc[1 + i][cb][tb] = Tr::mma(var[i & 1][cb], b[tb], acc[1 + i][cb][tb]);
+                    interleave(i + 1 < NMP);
+                }
+            } else if constexpr (TB == 2 && MODE != kModeSwiglu && MODE != kModeLinear) {
                 // Many masks, one pair of token blocks: each mask's operand is prepared right before its
                 // two MFMAs and dropped after them (all variants at once would not fit the registers);
                 // the issue-order groups keep the compiler from gathering the preparation up front.
@@ -296,15 +379,16 @@ void prefill_kernel(PrefillParams p)
                     if (more) { bcur[0] = bnxt[0]; bcur[1] = bnxt[1]; }
                 }
             }
-#pragma unroll
-            for (int s = 0; s < XPIECES; ++s)   // a piece is stored one tile after its load was issued
-                if (MGLU_PREFILL_XSTORE_TILE(s, XPIECES) == t)
-                    *x_dst((kc + kPrefillXAhead) & (kPrefillXBuf - 1), s) = xv[s];
         }
+        // the chunk's x fragments have landed in LDS once only the loads issued after the last of them
+        // may still be outstanding (the A fragments of the tiles from that one on, and the masks if
+        // that was the chunk's first tile)
+        constexpr int XL = MGLU_PREFILL_XLOAD_TILE(XPIECES - 1, XPIECES);
+        wait_vm(std::integral_constant<int, (4 - XL) * A_LOADS + (XL == 0 ? M_LOADS : 0)>{});
         // with two buffers every chunk ends in a barrier; with four only every second one (a buffer
         // is written two chunks after its last read and read two chunks after it was written, and
         // one barrier lies in between either way)
-        if (kPrefillXBuf == 2 || MS == 1) __syncthreads();
+        if (kPrefillXBuf == 2 || MS == 1) __builtin_amdgcn_s_barrier();
     };
 
     int kc = 0;
