@@ -33,7 +33,7 @@
 #define MGLU_PREFILL_AD4 2
 #endif
 #ifndef MGLU_PREFILL_TB4
-#define MGLU_PREFILL_TB4 6   // token blocks per workgroup tile for four masks
+#define MGLU_PREFILL_TB4 0   // token blocks per workgroup tile for four masks: 6, 8, or 0 = chosen per launch
 #endif
 
 namespace mglu {
@@ -68,8 +68,9 @@ void prefill_kernel(PrefillParams p)
     constexpr int SETS = sets_of(MODE, NMP);
     constexpr int AR = 4;                       // ring entries (one per tile of a chunk)
     constexpr long CHUNK_BYTES = (long)kColBlock * kChunkK * 2;
-    constexpr int XPIECES = TB * 4 / kPrefillWaves;  // x fragments each wavefront stages per chunk
-    static_assert(TB * 4 % kPrefillWaves == 0, "token blocks must split evenly over the wavefronts");
+    // x fragments each wavefront stages per chunk (the last one only by the first wavefronts when the
+    // TB * 4 fragments do not split evenly)
+    constexpr int XPIECES = (TB * 4 + kPrefillWaves - 1) / kPrefillWaves;
     extern __shared__ f32x4 lds_raw[];
     frag *lds_x = reinterpret_cast<frag *>(lds_raw);   // [2][tile t<4][tb<TB][lane<64]
     // byte address of that array inside LDS, for the hand-placed reads
@@ -146,7 +147,8 @@ void prefill_kernel(PrefillParams p)
         const int tb = idx >> 2, t = idx & 3;
         const uint32_t kb = min((uint32_t)(kc * kChunkK + 32 * t) * 2 + q * 16, klim);
         frag *dst = lds_x + ((buf * 4 + t) * TB + tb) * kWave;   // uniform over the wavefront
-        __builtin_amdgcn_raw_ptr_buffer_load_lds(xrsrc, (__attribute__((address_space(3))) void *)dst, 16,
+        if (TB * 4 % kPrefillWaves == 0 || idx < TB * 4)   // uniform; skipping the last piece only makes the wait below stricter
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(xrsrc, (__attribute__((address_space(3))) void *)dst, 16,
                                                  (int)(xrow[s] + kb), 0, 0, 0);
     };
 
@@ -224,7 +226,6 @@ void prefill_kernel(PrefillParams p)
         // (the compiler, left alone, issues each read right before its use and eats the LDS latency
         // three times per tile).  The first pair of a chunk cannot be fetched before the barrier.
         constexpr int PAIRS = TB / 2;
-        static_assert(TB % 2 == 0, "token blocks are processed in pairs");
         // The reads are written as assembly so that they stay where they are put; the matching
         // waits name the registers they release, which orders every use after them.  (lgkmcnt
         // counts LDS operations in order, so "at most 2 newer ones outstanding" means the pair
@@ -238,7 +239,9 @@ void prefill_kernel(PrefillParams p)
         // parity, and the sets are multiplied one after the other -- so mask i + 1's operand is prepared
         // in the issue slots between the MFMAs of mask i instead of ahead of the whole tile.  Worth
         // about 1 % there; with eight masks the second set of B fragments no longer fits the registers.
-        constexpr bool MASK_MAJOR = kPrefillMaskMajor && TB == 6 && MODE != kModeSwiglu && MODE != kModeLinear;
+        constexpr bool MASK_MAJOR =
+            kPrefillMaskMajor && (TB == 6 || TB == 3) && MODE != kModeSwiglu && MODE != kModeLinear;
+        static_assert(TB % 2 == 0 || MASK_MAJOR, "token blocks are processed in pairs");
         auto read_tile = [&](frag (&b)[TB], int t) __attribute__((always_inline)) {
 #pragma unroll
             for (int tb = 0; tb < TB; ++tb)
@@ -466,6 +469,22 @@ static hipError_t launch_prefill_one(PrefillParams p, hipStream_t stream)
     return hipGetLastError();
 }
 
+// Four masks: a tile of 128 tokens (fewer loads of W per multiply: 3-8 % faster on full launches) or of
+// 96 tokens (mask-major order; fewer wasted rows and more workgroups when the launch is small).  The
+// choice minimises rounds of workgroups over the chip x work per workgroup.
+template <typename Tr, int MODE>
+static hipError_t launch_prefill_four(const PrefillParams &p, hipStream_t stream)
+{
+    constexpr long kChipCUs = 256;
+    auto cost = [&](int tb) {
+        const long wgs = ceil_div(p.T, 16 * tb) * ceil_div(p.d, kPrefillWaves * kColBlock);
+        return (double)ceil_div(wgs, kChipCUs) * tb * (tb == 6 ? 1.05 : 1.0);
+    };
+    const int tb = MGLU_PREFILL_TB4 ? MGLU_PREFILL_TB4 : (cost(8) <= cost(6) ? 8 : 6);
+    if (tb == 8) return launch_prefill_one<Tr, 4, 1, 8, MODE, MGLU_PREFILL_AD4>(p, stream);
+    return launch_prefill_one<Tr, 4, 1, 6, MODE, MGLU_PREFILL_AD4>(p, stream);
+}
+
 template <typename Tr>
 static hipError_t launch_prefill_t(const PrefillParams &p, int mode, hipStream_t stream)
 {
@@ -475,7 +494,7 @@ static hipError_t launch_prefill_t(const PrefillParams &p, int mode, hipStream_t
         switch (round_up_masks(p.n_masks)) {
         case 1: return launch_prefill_one<Tr, 1, 2, 8, kModeMgluVariant, 1>(p, stream);
         case 2: return launch_prefill_one<Tr, 2, 1, 8, kModeMgluVariant, 2>(p, stream);
-        case 4: return launch_prefill_one<Tr, 4, 1, MGLU_PREFILL_TB4, kModeMgluVariant, MGLU_PREFILL_AD4>(p, stream);
+        case 4: return launch_prefill_four<Tr, kModeMgluVariant>(p, stream);
         case 8: return launch_prefill_one<Tr, 8, 1, 4, kModeMgluVariant, 2>(p, stream);
         default: return launch_prefill_one<Tr, 16, 1, 2, kModeMgluVariant, 2>(p, stream);
         }
@@ -483,7 +502,7 @@ static hipError_t launch_prefill_t(const PrefillParams &p, int mode, hipStream_t
     switch (round_up_masks(p.n_masks)) {
     case 1: return launch_prefill_one<Tr, 1, 2, 8, kModeMglu, 1>(p, stream);
     case 2: return launch_prefill_one<Tr, 2, 1, 8, kModeMglu, 2>(p, stream);
-    case 4: return launch_prefill_one<Tr, 4, 1, MGLU_PREFILL_TB4, kModeMglu, MGLU_PREFILL_AD4>(p, stream);
+    case 4: return launch_prefill_four<Tr, kModeMglu>(p, stream);
     case 8: return launch_prefill_one<Tr, 8, 1, 4, kModeMglu, 2>(p, stream);
     default: return launch_prefill_one<Tr, 16, 1, 2, kModeMglu, 2>(p, stream);
     }

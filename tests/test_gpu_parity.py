@@ -75,6 +75,21 @@ def test_prefill_kernel_ragged_shapes(T, h, d, n_m):
     _check_full(x, W, masks, _run(x, W, masks))
 
 
+@pytest.mark.parametrize("dtype,T,h,d,n_m", [
+    ("bf16", 1000, 320, 4000, 4), ("bf16", 1000, 136, 4090, 3), ("f16", 1000, 264, 4000, 4), ("bf16", 250, 256, 16300, 4),
+])
+def test_prefill_four_masks_tall_tile(dtype, T, h, d, n_m):
+    """With three or four masks the tiled kernel picks a 96- or a 128-token tile per launch (whichever
+    covers the chip in less work).  These launches are large enough for the 128-token tile -- the small
+    ragged shapes above all take the 96-token one -- with ragged token, column and reduction tails."""
+    x, W, masks = synth.make_inputs(h, d, n_m, T, dtype=dtype, seed=T + h + d, device=DEV)
+    out = _run(x, W, masks)
+    if d > 4096:
+        _check_columns(x, W, masks, out, edge_columns(d, n_random=256, seed=T))
+    else:
+        _check_full(x, W, masks, out)
+
+
 @pytest.mark.parametrize("T,h,d,n_m", [(40, 384, 25616, 2), (200, 520, 272, 4), (300, 384, 1000, 8), (129, 1024, 130, 1)])
 def test_fp16_panel_and_tiled_kernels(T, h, d, n_m):
     """fp16, the paper's own precision, through the panel kernel and the MFMA-tiled kernel."""

@@ -127,6 +127,22 @@ def test_sixteen_masks_routed_top4_gelu(T):
     assert rel_err(to_np64(out), ref) <= TOL[x.dtype]
 
 
+def test_variant_four_masks_tall_tile():
+    """A launch large enough for the 128-token tile of the four-mask tiled kernel, in the variant mode:
+    top-2 routing of 4 masks with a GELU gate, ragged tails."""
+    h, d, n_m, T = 264, 4000, 4, 1000
+    x, W, masks = synth.make_inputs(h, d, n_m, T, dtype="bf16", seed=41, device=DEV)
+    gen = torch.Generator(device=DEV).manual_seed(9)
+    Wr = (torch.randn(h, n_m, generator=gen, device=DEV) * 0.1).to(x.dtype)
+    desc, Wp, Mp = _packed(x, W, masks)
+    w = api.mglu_route_topk(desc, x, Wr, 2)
+    out = api.mglu_forward_variant(desc, x, Wp, Mp, gate="gelu", route_weights=w)
+    ref = oracle.mglu_forward_variant(to_np64(x), to_np64(W), masks.cpu().numpy(), gate="gelu", route=to_np64(w))
+    assert rel_err(to_np64(out), ref) <= TOL[x.dtype]
+    ones = torch.ones(T, n_m, dtype=torch.float32, device=DEV)
+    assert torch.equal(api.mglu_forward_variant(desc, x, Wp, Mp, route_weights=ones), api.mglu_forward(desc, x, Wp, Mp))
+
+
 @pytest.mark.parametrize("dtype,T", [("bf16", 1), ("bf16", 32), ("bf16", 200), ("f32", 3), ("f16", 5), ("f16", 120)])
 def test_linear_projection(dtype, T):
     K, N = 656, 272
