@@ -153,6 +153,17 @@ def test_linear_projection(dtype, T):
     assert rel_err(to_np64(out), ref) <= TOL[a.dtype]
 
 
+def test_linear_projection_wide_tile():
+    """A projection large enough for the tiled kernel's 512-column tile (the small ones above take the
+    256-column tile), with ragged token, column and reduction tails."""
+    T, K, N = 2100, 264, 4000
+    a, W, _ = synth.make_inputs(K, N, 1, T, dtype="bf16", seed=5, device=DEV)
+    desc = api.make_desc(T, K, N, 1, a.dtype)
+    out = api.mglu_linear_forward(desc, a, api.mglu_pack_weights(desc, W))
+    ref = oracle.linear_forward(to_np64(a), to_np64(W))
+    assert rel_err(to_np64(out), ref) <= TOL[a.dtype]
+
+
 @pytest.mark.parametrize("T", [1, 16, 96])
 def test_whole_ffn_block(T):
     """y = MGLU(x) Wo.  The GPU rounds the intermediate representation to bf16 between the two
