@@ -93,9 +93,14 @@ mglu::StreamParams stream_params(const mglu_desc *d)
     return p;
 }
 
-// Token counts above this go to the MFMA-tiled prefill kernel (bf16); at or below it the
-// layer is bound by streaming W and runs on the streaming kernel.
-constexpr int kStreamMaxTokens = 64;
+// Token counts the streaming kernels cover in one pass over W (64 with one or two masks, 32 with up to
+// eight, 16 beyond) stay on them: there the layer is bound by streaming W.  Above that the 16-bit types
+// go to the MFMA-tiled kernel, whose small tile shapes fill the chip from a few dozen tokens on.
+bool use_tiled_kernel(const mglu_desc *d, int n_masks)
+{
+    if (d->dtype == MGLU_F32) return false;
+    return d->tokens > 16 * mglu::stream_max_token_blocks(mglu::round_up_masks(n_masks), elem_of(d));
+}
 
 mglu::PrefillParams prefill_params(const mglu_desc *d)
 {
@@ -201,7 +206,7 @@ mglu_status mglu_forward_variant(const mglu_desc *desc, const mglu_variant *vari
     }
     // the main form (Swish, both branches masked, no route weights) runs the kernels without the run-time choices
     const int mode = (gate_fn != 0 || mask_use != 0 || route) ? mglu::kModeMgluVariant : mglu::kModeMglu;
-    if (desc->dtype != MGLU_F32 && desc->tokens > kStreamMaxTokens) {
+    if (use_tiled_kernel(desc, desc->n_masks)) {
         mglu::PrefillParams pp = prefill_params(desc);
         pp.x = x_dev;
         pp.w = W_packed_dev;
@@ -269,7 +274,7 @@ mglu_status mglu_linear_forward(const mglu_desc *desc, const void *a_dev, const 
     MGLU_TRY(check_ptr(out_dev, "out_dev"));
     (void)workspace_dev;
     (void)workspace_bytes;
-    if (desc->dtype != MGLU_F32 && desc->tokens > kStreamMaxTokens) {
+    if (use_tiled_kernel(desc, 1)) {
         mglu::PrefillParams pp = prefill_params(desc);
         pp.x = a_dev;
         pp.w = W_packed_dev;
@@ -364,7 +369,7 @@ mglu_status swiglu_forward(const mglu_desc *desc, const void *x_dev, const void 
     MGLU_TRY(check_ptr(out_dev, "out_dev"));
     (void)workspace_dev;
     (void)workspace_bytes;
-    if (desc->dtype != MGLU_F32 && desc->tokens > kStreamMaxTokens) {
+    if (use_tiled_kernel(desc, 1)) {
         mglu::PrefillParams pp = prefill_params(desc);
         pp.x = x_dev;
         pp.w = Wg_packed_dev;

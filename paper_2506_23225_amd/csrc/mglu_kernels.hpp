@@ -3,6 +3,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include "mglu_common.hpp"
+
 namespace mglu {
 
 struct StreamParams {
@@ -51,6 +53,11 @@ struct PackParams {
     int NB, NC;
     int nk;               // 0: [h][d] (masks [n][h][d]); 1: [d][h] (masks [n][d][h])
 };
+
+// Largest token-block count (blocks of 16 tokens) a workgroup of the streaming kernels handles per pass over W:
+// what the 256-register budget of the panel kernel allows.  Beyond 16 x this many tokens the streaming kernels
+// would read W once per group of token blocks, and the 16-bit types hand over to the MFMA-tiled kernel.
+inline int stream_max_token_blocks(int nmp, int elem) { return elem == kElemF32 || nmp > 8 ? 1 : nmp <= 2 ? 4 : 2; }
 
 // `elem` is an Elem (mglu_common.hpp): the element type of x, W and out
 hipError_t launch_stream(const StreamParams &p, int elem, int mode, hipStream_t stream);

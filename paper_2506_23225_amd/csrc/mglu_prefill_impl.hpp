@@ -9,13 +9,13 @@
 // worth of work instead of the 2 n_m of the naive form, and W, the masks and x are each
 // staged once per tile for all of them.
 //
-// Tiling (one workgroup = 8 wavefronts = one CU at 2 wavefronts per SIMD):
-//   workgroup tile  BM = 16*TB tokens  x  BN = 8*16*CB columns
+// Tiling (one workgroup = NW = 8 wavefronts = one CU at 2 wavefronts per SIMD, or NW = 4 and two per CU):
+//   workgroup tile  BM = 16*TB tokens  x  BN = NW*16*CB columns
 //   wavefront w owns CB column blocks of 16 columns, for all BM tokens
 //   A operand (W): streamed straight from global memory in the packed tile order -- each
 //     wavefront reads only its own column blocks, so LDS staging would buy no reuse
 //   masks: read next to W, one chunk (128 k) of words at a time, applied in registers
-//   B operand (x): shared by all 8 wavefronts -> staged through LDS in B-fragment order by loads
+//   B operand (x): shared by all wavefronts -> staged through LDS in B-fragment order by loads
 //     that go from global memory straight to LDS (no registers, no LDS write instructions),
 //     double-buffered per 128-k chunk, one barrier per chunk
 //   MFMA: v_mfma_f32_16x16x32_bf16, 16 columns x 16 tokens per accumulator
@@ -27,13 +27,8 @@
 #include "mglu_common.hpp"
 #include "mglu_kernels.hpp"
 
-// Tile shapes per mask count, chosen so that the accumulators plus the operand ring stay
-// inside the 256 registers a wavefront has at 2 wavefronts per SIMD (no scratch).
-#ifndef MGLU_PREFILL_AD4
-#define MGLU_PREFILL_AD4 2
-#endif
-#ifndef MGLU_PREFILL_TB4
-#define MGLU_PREFILL_TB4 0   // token blocks per workgroup tile for four masks: 6, 8, or 0 = chosen per launch
+#ifndef MGLU_PREFILL_AD_SMALL
+#define MGLU_PREFILL_AD_SMALL 6   // tiles of W fetched ahead in the 4-wavefront shapes that have the registers for it
 #endif
 
 namespace mglu {
@@ -42,10 +37,6 @@ namespace mglu {
 #ifndef MGLU_PREFILL_XLOAD_TILE
 #define MGLU_PREFILL_XLOAD_TILE(s, n) ((s) * 3 / (n))
 #endif
-#ifndef MGLU_PREFILL_WAVES
-#define MGLU_PREFILL_WAVES 8   // wavefronts per workgroup (8: one workgroup per CU; 4: two)
-#endif
-constexpr int kPrefillWaves = MGLU_PREFILL_WAVES;
 // LDS buffers of one chunk of x each.  2: a chunk is staged while the one before it is multiplied, one
 // barrier per chunk.  4: staged two chunks ahead, one barrier per two chunks, so that the wavefronts
 // of a workgroup may drift a chunk apart instead of meeting after every chunk.
@@ -60,17 +51,24 @@ constexpr bool kPrefillMaskMajor = MGLU_PREFILL_MASK_MAJOR;
 constexpr int kPrefillXAhead = kPrefillXBuf / 2;   // chunks between staging and use
 
 // AD: how many tiles ahead of the multiply the A fragments are fetched.
-template <typename Tr, int NMP, int CB, int TB, int MODE, int AD>
-__global__ __launch_bounds__(kPrefillWaves *kWave) __attribute__((amdgpu_waves_per_eu(2, 2)))
+// NW: wavefronts per workgroup.  8: one workgroup fills a CU (2 wavefronts per SIMD).  4: a CU holds two, and
+// a launch of at most 256 such workgroups gives every wavefront a SIMD of its own -- for launches that would
+// otherwise leave CUs idle while the busy ones run two wavefronts per SIMD.
+template <typename Tr, int NMP, int CB, int TB, int MODE, int AD, int NW>
+__global__ __launch_bounds__(NW *kWave) __attribute__((amdgpu_waves_per_eu(2, 2)))
 void prefill_kernel(PrefillParams p)
 {
     typedef typename Tr::frag frag;
     constexpr int SETS = sets_of(MODE, NMP);
-    constexpr int AR = 4;                       // ring entries (one per tile of a chunk)
+    // ring entries: the tiles of one chunk, or of two chunks for a deep prefetch (a ring of four chunks with
+    // the masks fetched as far ahead was measured too: no faster)
+    constexpr int AR = AD <= 3 ? 4 : 8;
+    constexpr int MR = 2;                       // mask ring entries (chunks): this chunk's and the next one's
+    static_assert(AD < AR, "the fragment being multiplied must not be overwritten");
     constexpr long CHUNK_BYTES = (long)kColBlock * kChunkK * 2;
     // x fragments each wavefront stages per chunk (the last one only by the first wavefronts when the
     // TB * 4 fragments do not split evenly)
-    constexpr int XPIECES = (TB * 4 + kPrefillWaves - 1) / kPrefillWaves;
+    constexpr int XPIECES = (TB * 4 + NW - 1) / NW;
     extern __shared__ f32x4 lds_raw[];
     frag *lds_x = reinterpret_cast<frag *>(lds_raw);   // [2][tile t<4][tb<TB][lane<64]
     // byte address of that array inside LDS, for the hand-placed reads
@@ -100,7 +98,7 @@ void prefill_kernel(PrefillParams p)
         if (tile_m >= p.tiles_m || tile_n >= p.tiles_n || in_patch / rows >= per_xcd) return;
     }
     const int tok0 = tile_m * (16 * TB);
-    const int jb0 = (tile_n * kPrefillWaves + wave) * CB;   // first column block of this wavefront
+    const int jb0 = (tile_n * NW + wave) * CB;   // first column block of this wavefront
 
     // column blocks past the end are clamped for the loads and dropped at the store
     const char *wbase[CB];       // scalar: start of the column block's weight stream
@@ -133,7 +131,7 @@ void prefill_kernel(PrefillParams p)
     uint32_t xrow[XPIECES];      // per piece: byte offset of this lane's token row from xbase
 #pragma unroll
     for (int s = 0; s < XPIECES; ++s) {
-        const int tb = (wave + kPrefillWaves * s) >> 2;
+        const int tb = (wave + NW * s) >> 2;
         xrow[s] = (uint32_t)(min(tok0 + 16 * tb + r, p.T - 1) - tok0) * (uint32_t)(p.h * 2);
     }
     // One fragment of x goes from global memory straight to LDS (no registers in between): the load
@@ -143,11 +141,11 @@ void prefill_kernel(PrefillParams p)
     const __amdgpu_buffer_rsrc_t xrsrc = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<char *>(xbase), 0, (min(tok0 + 16 * TB, p.T) - tok0) * p.h * 2, 0x00020000);
     auto stage_x = [&](int kc, int buf, int s) __attribute__((always_inline)) {
-        const int idx = wave + kPrefillWaves * s;
+        const int idx = wave + NW * s;
         const int tb = idx >> 2, t = idx & 3;
         const uint32_t kb = min((uint32_t)(kc * kChunkK + 32 * t) * 2 + q * 16, klim);
         frag *dst = lds_x + ((buf * 4 + t) * TB + tb) * kWave;   // uniform over the wavefront
-        if (TB * 4 % kPrefillWaves == 0 || idx < TB * 4)   // uniform; skipping the last piece only makes the wait below stricter
+        if (TB * 4 % NW == 0 || idx < TB * 4)   // uniform; skipping the last piece only makes the wait below stricter
             __builtin_amdgcn_raw_ptr_buffer_load_lds(xrsrc, (__attribute__((address_space(3))) void *)dst, 16,
                                                  (int)(xrow[s] + kb), 0, 0, 0);
     };
@@ -155,7 +153,7 @@ void prefill_kernel(PrefillParams p)
     // ---- A ring: entry t holds the fragments of tile t of the current (or next) chunk ----
     frag aw[AR][CB];
     frag aw2[MODE == kModeSwiglu ? AR : 1][CB];
-    uint32_t mk[2][CB][NMP];   // mask words of the current and the next chunk
+    uint32_t mk[MR][CB][NMP];  // mask words of the current chunk and the MR - 1 after it
 
     auto load_a = [&](int kc, int t, int slot) __attribute__((always_inline)) {
 #pragma unroll
@@ -207,20 +205,24 @@ void prefill_kernel(PrefillParams p)
 #pragma unroll
             for (int s = 0; s < XPIECES; ++s) stage_x(min(c, last), c, s);
         __builtin_amdgcn_sched_barrier(0);   // the x loads stay the oldest ones in flight
-        load_masks(0, 0);
 #pragma unroll
-        for (int t = 0; t < AD; ++t) load_a(0, t, t);
+        for (int c = 0; c < MR - 1; ++c) load_masks(min(c, last), c);
+#pragma unroll
+        for (int t = 0; t < AD; ++t) load_a(min(t / 4, last), t % 4, t % AR);
     }
     // Loads complete in issue order, so "at most the loads issued after them outstanding" means the x
     // fragments are in LDS; the compiler does not know that the hand-placed LDS reads depend on them.
-    wait_vm(std::integral_constant<int, M_LOADS + AD * A_LOADS>{});
+    wait_vm(std::integral_constant<int, (MR - 1) * M_LOADS + AD * A_LOADS>{});
     __builtin_amdgcn_s_barrier();
 
-    // One chunk of the K loop; MS = which half of mk[] holds this chunk's masks (compile time).
-    auto chunk_step = [&](int kc, auto ms_tag) __attribute__((always_inline)) {
-        constexpr int MS = decltype(ms_tag)::value;
+    // One chunk of the K loop; PHASE = kc modulo the unroll (compile time): it fixes which entry of mk[]
+    // holds this chunk's masks and where its tiles sit in the ring.
+    auto chunk_step = [&](int kc, auto phase_tag) __attribute__((always_inline)) {
+        constexpr int PHASE = decltype(phase_tag)::value;
+        constexpr int MS = PHASE % MR;
+        constexpr int RS = (4 * PHASE) % AR;       // ring slot of this chunk's first tile
         const int buf = kc & (kPrefillXBuf - 1);
-        const int kn = min(kc + 1, last);   // next chunk, clamped: its loads are then always in bounds
+        const int kn = min(kc + MR - 1, last);   // the chunk whose masks are fetched now, clamped: always in bounds
         const int kx = min(kc + kPrefillXAhead, last);   // the chunk of x staged during this one
         // B fragments are read from LDS one pair of token blocks ahead of the MFMAs that use them
         // (the compiler, left alone, issues each read right before its use and eats the LDS latency
@@ -266,9 +268,8 @@ void prefill_kernel(PrefillParams p)
                 if (MGLU_PREFILL_XLOAD_TILE(s, XPIECES) == t)
                     stage_x(kx, (kc + kPrefillXAhead) & (kPrefillXBuf - 1), s);
             __builtin_amdgcn_sched_barrier(0);   // x first: the wait at the end of the chunk counts on it
-            if (t + AD < 4) load_a(kc, t + AD, (t + AD) % AR);
-            else load_a(kn, t + AD - 4, (t + AD) % AR);
-            if (t == 0) load_masks(kn, MS ^ 1);
+            load_a(min(kc + (t + AD) / 4, last), (t + AD) % 4, (RS + t + AD) % AR);
+            if (t == 0) load_masks(kn, (MS + MR - 1) % MR);
             __builtin_amdgcn_sched_barrier(0);
 
             if constexpr (MASK_MAJOR) {
@@ -289,14 +290,14 @@ void prefill_kernel(PrefillParams p)
                     }
                 };
 #pragma unroll
-                for (int cb = 0; cb < CB; ++cb) var[0][cb] = Tr::template flip<NMP>(aw[t][cb], mk[MS][cb], t, 0);
+                for (int cb = 0; cb < CB; ++cb) var[0][cb] = Tr::template flip<NMP>(aw[(RS + t) % AR][cb], mk[MS][cb], t, 0);
                 if (t == 0) {
                     // this tile's reads were issued right after the barrier: take the fragments as they land
 #pragma unroll
                     for (int tb = 0; tb < TB; ++tb) {
                         wait_frag(b[tb], TB - 1 - tb);
 #pragma unroll
-                        for (int cb = 0; cb < CB; ++cb) acc[0][cb][tb] = Tr::mma(aw[t][cb], b[tb], acc[0][cb][tb]);
+                        for (int cb = 0; cb < CB; ++cb) acc[0][cb][tb] = Tr::mma(aw[(RS + t) % AR][cb], b[tb], acc[0][cb][tb]);
                     }
                     read_tile(btile[1], 1);
                 } else {
@@ -307,7 +308,7 @@ void prefill_kernel(PrefillParams p)
 #pragma unroll
                     for (int tb = 0; tb < TB; ++tb)
 #pragma unroll
-                        for (int cb = 0; cb < CB; ++cb) acc[0][cb][tb] = Tr::mma(aw[t][cb], b[tb], acc[0][cb][tb]);
+                        for (int cb = 0; cb < CB; ++cb) acc[0][cb][tb] = Tr::mma(aw[(RS + t) % AR][cb], b[tb], acc[0][cb][tb]);
                 }
                 interleave(true);
 #pragma unroll
@@ -315,7 +316,7 @@ void prefill_kernel(PrefillParams p)
                     if (i + 1 < NMP) {
 #pragma unroll
                         for (int cb = 0; cb < CB; ++cb)
-                            var[(i + 1) & 1][cb] = Tr::template flip<NMP>(aw[t][cb], mk[MS][cb], t, i + 1);
+                            var[(i + 1) & 1][cb] = Tr::template flip<NMP>(aw[(RS + t) % AR][cb], mk[MS][cb], t, i + 1);
                     }
 #pragma unroll
                     for (int tb = 0; tb < TB; ++tb)
@@ -338,11 +339,11 @@ void prefill_kernel(PrefillParams p)
 #pragma unroll
                 for (int cb = 0; cb < CB; ++cb) {
 #pragma unroll
-                    for (int h2 = 0; h2 < 2; ++h2) acc[0][cb][h2] = Tr::mma(aw[t][cb], bcur[h2], acc[0][cb][h2]);
+                    for (int h2 = 0; h2 < 2; ++h2) acc[0][cb][h2] = Tr::mma(aw[(RS + t) % AR][cb], bcur[h2], acc[0][cb][h2]);
                     __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
 #pragma unroll
                     for (int i = 0; i < NMP; ++i) {
-                        const frag wf = Tr::template flip<NMP>(aw[t][cb], mk[MS][cb], t, i);
+                        const frag wf = Tr::template flip<NMP>(aw[(RS + t) % AR][cb], mk[MS][cb], t, i);
 #pragma unroll
                         for (int h2 = 0; h2 < 2; ++h2) acc[1 + i][cb][h2] = Tr::mma(wf, bcur[h2], acc[1 + i][cb][h2]);
                         __builtin_amdgcn_sched_group_barrier(0x002, 8, 0);
@@ -355,12 +356,12 @@ void prefill_kernel(PrefillParams p)
                 frag var[SETS][CB];
     #pragma unroll
                 for (int cb = 0; cb < CB; ++cb) {
-                    var[0][cb] = aw[t][cb];
+                    var[0][cb] = aw[(RS + t) % AR][cb];
                     if constexpr (MODE == kModeSwiglu) {
-                        var[1][cb] = aw2[t][cb];
+                        var[1][cb] = aw2[(RS + t) % AR][cb];
                     } else if constexpr (MODE != kModeLinear) {
     #pragma unroll
-                        for (int i = 0; i < NMP; ++i) var[1 + i][cb] = Tr::template flip<NMP>(aw[t][cb], mk[MS][cb], t, i);
+                        for (int i = 0; i < NMP; ++i) var[1 + i][cb] = Tr::template flip<NMP>(aw[(RS + t) % AR][cb], mk[MS][cb], t, i);
                     }
                 }
     #pragma unroll
@@ -391,11 +392,12 @@ void prefill_kernel(PrefillParams p)
         // with two buffers every chunk ends in a barrier; with four only every second one (a buffer
         // is written two chunks after its last read and read two chunks after it was written, and
         // one barrier lies in between either way)
-        if (kPrefillXBuf == 2 || MS == 1) __builtin_amdgcn_s_barrier();
+        if (kPrefillXBuf == 2 || (PHASE & 1) == 1) __builtin_amdgcn_s_barrier();
     };
 
+    // the loop body covers two chunks, so that every chunk's place in the rings is known at compile time
     int kc = 0;
-    for (; kc + 1 < p.NC; kc += 2) {
+    for (; kc + 2 <= p.NC; kc += 2) {
         chunk_step(kc, std::integral_constant<int, 0>{});
         chunk_step(kc + 1, std::integral_constant<int, 1>{});
     }
@@ -448,10 +450,10 @@ void prefill_kernel(PrefillParams p)
 
 // ---- host side --------------------------------------------------------------------------------
 
-template <typename Tr, int NMP, int CB, int TB, int MODE, int AD>
+template <typename Tr, int NMP, int CB, int TB, int MODE, int AD, int NW>
 static hipError_t launch_prefill_one(PrefillParams p, hipStream_t stream)
 {
-    const int bm = 16 * TB, bn = kPrefillWaves * kColBlock * CB;
+    const int bm = 16 * TB, bn = NW * kColBlock * CB;
     p.tiles_m = (int)ceil_div(p.T, bm);
     p.tiles_n = (int)ceil_div(p.d, bn);
     p.group_m = p.tiles_m < 8 ? p.tiles_m : 8;
@@ -459,68 +461,91 @@ static hipError_t launch_prefill_one(PrefillParams p, hipStream_t stream)
     const int per_xcd = (p.tiles_n + 7) / 8;
     const long wgs = (long)8 * per_xcd * p.tiles_m;
     const size_t lds = (size_t)kPrefillXBuf * 4 * TB * kWave * sizeof(f32x4);
-    auto kern = prefill_kernel<Tr, NMP, CB, TB, MODE, AD>;
+    auto kern = prefill_kernel<Tr, NMP, CB, TB, MODE, AD, NW>;
     if (lds > 64 * 1024) {   // beyond the default dynamic LDS limit: allowed once per kernel
         static hipError_t allowed = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                                                         hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         if (allowed != hipSuccess) return allowed;
     }
-    hipLaunchKernelGGL(kern, dim3((unsigned)wgs), dim3(kPrefillWaves * kWave), lds, stream, p);
+    hipLaunchKernelGGL(kern, dim3((unsigned)wgs), dim3(NW * kWave), lds, stream, p);
     return hipGetLastError();
 }
 
-// Four masks: a tile of 128 tokens (fewer loads of W per multiply: 3-8 % faster on full launches) or of
-// 96 tokens (mask-major order; fewer wasted rows and more workgroups when the launch is small).  The
-// choice minimises rounds of workgroups over the chip x work per workgroup.
-template <typename Tr, int MODE>
-static hipError_t launch_prefill_four(const PrefillParams &p, hipStream_t stream)
+// ---- tile shape per launch ---------------------------------------------------------------------
+// A wavefront's tile is 16 CB columns x 16 TB tokens, a workgroup's NW times as wide.  Taller and wider
+// tiles load W and x less often per multiply, and that is what the loop's speed (and the clock the chip
+// holds) responds to; smaller tiles and 4-wavefront workgroups fill the chip when the launch is small.
+// Each kernel family lists its shapes, largest first; the launcher takes the one with the least
+// estimated time: per-wavefront work x the wavefronts that share the busiest SIMD, one after the other.
+// AD: tiles of W fetched ahead.  2 where workgroups of several token tiles share W through L2; 6 (an
+// 8-entry ring) in the 4-wavefront shapes, whose launches have one or two token tiles and stream W
+// straight from HBM with a single wavefront per SIMD to cover its latency.
+template <int CB_, int TB_, int NW_, int AD_>
+struct Tile { static constexpr int CB = CB_, TB = TB_, NW = NW_, AD = AD_; };
+
+template <typename S>
+static double prefill_cost(const PrefillParams &p)
 {
     constexpr long kChipCUs = 256;
-    auto cost = [&](int tb) {
-        const long wgs = ceil_div(p.T, 16 * tb) * ceil_div(p.d, kPrefillWaves * kColBlock);
-        return (double)ceil_div(wgs, kChipCUs) * tb * (tb == 6 ? 1.05 : 1.0);
-    };
-    const int tb = MGLU_PREFILL_TB4 ? MGLU_PREFILL_TB4 : (cost(8) <= cost(6) ? 8 : 6);
-    if (tb == 8) return launch_prefill_one<Tr, 4, 1, 8, MODE, MGLU_PREFILL_AD4>(p, stream);
-    return launch_prefill_one<Tr, 4, 1, 6, MODE, MGLU_PREFILL_AD4>(p, stream);
+    const long wgs = ceil_div(p.T, 16 * S::TB) * ceil_div(p.d, S::NW * kColBlock * S::CB);
+    const double work = S::TB * S::CB;   // MFMAs of a wavefront per k step and accumulator set
+    double t;
+    if (S::NW == 8) {
+        t = (double)ceil_div(wgs, kChipCUs) * 2.0 * work;   // one workgroup per CU, two wavefronts per SIMD
+    } else {
+        // two workgroups per CU; up to 256 of them get a CU each (a wavefront alone on its SIMD runs a
+        // little below twice the speed of two that share one)
+        const long full = wgs / (2 * kChipCUs), rest = wgs % (2 * kChipCUs);
+        t = full * 2.0 * work + (rest == 0 ? 0.0 : rest <= kChipCUs ? 1.2 * work : 2.0 * work);
+        t *= 1.03;                                           // x is staged twice as often per multiply
+    }
+    // fewer multiplies per loaded fragment: measured 3-8 % from 96 to 128 tokens at four masks
+    return t * (work >= 8 ? 1.0 : work >= 6 ? 1.05 : 1.12);
 }
 
-// Plain projection (one accumulator set): a wavefront owns 4 column blocks (512-column tiles: twice the
-// MFMAs per loaded fragment, 51-53 % of peak instead of 40-43 % on the 14336 -> 4096 projection) unless
-// the launch is so small that 256-column tiles cover the chip in less work.
-template <typename Tr>
-static hipError_t launch_prefill_linear(const PrefillParams &p, hipStream_t stream)
+template <typename Tr, int NMP, int MODE, typename... Shapes>
+static hipError_t launch_prefill_best(const PrefillParams &p, hipStream_t stream)
 {
-    constexpr long kChipCUs = 256;
-    auto cost = [&](int cb) {
-        const long wgs = ceil_div(p.T, 16 * 8) * ceil_div(p.d, kPrefillWaves * kColBlock * cb);
-        return (double)ceil_div(wgs, kChipCUs) * cb * (cb == 2 ? 1.2 : 1.0);
+    int best = 0, i = 0;
+    double best_cost = 0.0;
+    auto consider = [&](double c) {
+        if (i == 0 || c < best_cost) { best = i; best_cost = c; }   // ties go to the earlier (larger) shape
+        ++i;
     };
-    if (cost(4) <= cost(2)) return launch_prefill_one<Tr, 1, 4, 8, kModeLinear, 2>(p, stream);
-    return launch_prefill_one<Tr, 1, 2, 8, kModeLinear, 2>(p, stream);
+    (consider(prefill_cost<Shapes>(p)), ...);
+    hipError_t result = hipErrorInvalidValue;
+    i = 0;
+    auto launch_if = [&](auto shape) {
+        typedef decltype(shape) S;
+        if (i++ == best) result = launch_prefill_one<Tr, NMP, S::CB, S::TB, MODE, S::AD, S::NW>(p, stream);
+    };
+    (launch_if(Shapes{}), ...);
+    return result;
+}
+
+template <typename Tr, int MODE>
+static hipError_t launch_prefill_masks(const PrefillParams &p, hipStream_t stream)
+{
+    // accumulators (1 + n_m sets of CB x TB x 4 registers) must fit 256 registers with the operands
+    switch (round_up_masks(p.n_masks)) {
+    case 1: return launch_prefill_best<Tr, 1, MODE, Tile<2, 8, 8, 1>, Tile<2, 8, 4, MGLU_PREFILL_AD_SMALL>>(p, stream);
+    case 2: return launch_prefill_best<Tr, 2, MODE, Tile<1, 8, 8, 2>, Tile<1, 8, 4, MGLU_PREFILL_AD_SMALL>>(p, stream);
+    case 4: return launch_prefill_best<Tr, 4, MODE, Tile<1, 8, 8, 2>, Tile<1, 6, 8, 2>, Tile<1, 8, 4, 3>, Tile<1, 4, 4, MGLU_PREFILL_AD_SMALL>>(p, stream);
+    case 8: return launch_prefill_best<Tr, 8, MODE, Tile<1, 4, 8, 2>, Tile<1, 4, 4, 3>>(p, stream);
+    default: return launch_prefill_best<Tr, 16, MODE, Tile<1, 2, 8, 2>, Tile<1, 2, 4, 3>>(p, stream);
+    }
 }
 
 template <typename Tr>
 static hipError_t launch_prefill_t(const PrefillParams &p, int mode, hipStream_t stream)
 {
-    if (mode == kModeSwiglu) return launch_prefill_one<Tr, 1, 2, 8, kModeSwiglu, 1>(p, stream);
-    if (mode == kModeLinear) return launch_prefill_linear<Tr>(p, stream);
-    if (mode == kModeMgluVariant) {
-        switch (round_up_masks(p.n_masks)) {
-        case 1: return launch_prefill_one<Tr, 1, 2, 8, kModeMgluVariant, 1>(p, stream);
-        case 2: return launch_prefill_one<Tr, 2, 1, 8, kModeMgluVariant, 2>(p, stream);
-        case 4: return launch_prefill_four<Tr, kModeMgluVariant>(p, stream);
-        case 8: return launch_prefill_one<Tr, 8, 1, 4, kModeMgluVariant, 2>(p, stream);
-        default: return launch_prefill_one<Tr, 16, 1, 2, kModeMgluVariant, 2>(p, stream);
-        }
-    }
-    switch (round_up_masks(p.n_masks)) {
-    case 1: return launch_prefill_one<Tr, 1, 2, 8, kModeMglu, 1>(p, stream);
-    case 2: return launch_prefill_one<Tr, 2, 1, 8, kModeMglu, 2>(p, stream);
-    case 4: return launch_prefill_four<Tr, kModeMglu>(p, stream);
-    case 8: return launch_prefill_one<Tr, 8, 1, 4, kModeMglu, 2>(p, stream);
-    default: return launch_prefill_one<Tr, 16, 1, 2, kModeMglu, 2>(p, stream);
-    }
+    if (mode == kModeSwiglu) return launch_prefill_one<Tr, 1, 2, 8, kModeSwiglu, 1, 8>(p, stream);
+    // plain projection (one accumulator set): 4 column blocks per wavefront on full launches -- twice the MFMAs
+    // per loaded fragment, 51-53 % of peak instead of 40-43 % on the 14336 -> 4096 projection
+    if (mode == kModeLinear)
+        return launch_prefill_best<Tr, 1, kModeLinear, Tile<4, 8, 8, 2>, Tile<2, 8, 8, 2>, Tile<2, 8, 4, MGLU_PREFILL_AD_SMALL>>(p, stream);
+    if (mode == kModeMgluVariant) return launch_prefill_masks<Tr, kModeMgluVariant>(p, stream);
+    return launch_prefill_masks<Tr, kModeMglu>(p, stream);
 }
 
 }  // namespace mglu

@@ -641,8 +641,6 @@ void stream_panel_kernel(StreamParams p)
 
 // ---- host side --------------------------------------------------------------------------------
 
-// Largest token-block count per workgroup the 256-register budget allows in the panel kernel.
-inline int stream_max_token_blocks(int nmp, int elem) { return elem == kElemF32 || nmp > 8 ? 1 : nmp <= 2 ? 4 : 2; }
 
 struct PanelWide  { static constexpr int NWC = 8, NWK = 1, CPW = 2; };
 struct PanelSplit { static constexpr int NWC = 4, NWK = 2, CPW = 1; };

@@ -127,15 +127,17 @@ def test_fp16_paper_shape_sampled(T):
           _check_columns(x, W, masks, out, edge_columns(cfg["d_ff"], n_random=48 if T > 1 else 128)))
 
 
-def test_kernel_hand_over_at_64_tokens():
-    """64 tokens run on the streaming (panel) kernel, 65 on the MFMA-tiled one: both against the oracle,
-    and the shared rows against each other (they may differ by summation order only)."""
-    x, W, masks = synth.make_inputs(768, 272, 6, 65, dtype="bf16", seed=64, device=DEV)
-    out65 = _run(x, W, masks)
-    out64 = _run(x[:64].contiguous(), W, masks)
-    _check_full(x, W, masks, out65)
-    _check_full(x[:64], W, masks, out64)
-    assert rel_err(to_np64(out64), to_np64(out65[:64])) <= 1e-2
+@pytest.mark.parametrize("n_m,T", [(2, 64), (6, 32), (12, 16)])
+def test_kernel_hand_over(n_m, T):
+    """T tokens -- what the streaming (panel) kernel covers in one pass over W with this many masks -- run
+    on it, T + 1 on the MFMA-tiled one: both against the oracle, and the shared rows against each other
+    (they may differ by summation order only)."""
+    x, W, masks = synth.make_inputs(768, 272, n_m, T + 1, dtype="bf16", seed=64 + n_m, device=DEV)
+    more = _run(x, W, masks)
+    fewer = _run(x[:T].contiguous(), W, masks)
+    _check_full(x, W, masks, more)
+    _check_full(x[:T], W, masks, fewer)
+    assert rel_err(to_np64(fewer), to_np64(more[:T])) <= 1e-2
 
 
 def test_prefill_kernel_other_layout_and_entries():
