@@ -70,7 +70,8 @@ def test_wide_panel_shape_ragged(T, h, d, n_m):
     (257, 136, 2064, 1), (1100, 256, 300, 3), (96, 2048, 144, 8),
 ])
 def test_prefill_kernel_ragged_shapes(T, h, d, n_m):
-    """Token counts above 64 take the MFMA-tiled kernel: ragged token, column and reduction tails."""
+    """Token counts beyond one pass of the streaming kernels take the MFMA-tiled kernel: ragged token, column and
+    reduction tails."""
     x, W, masks = synth.make_inputs(h, d, n_m, T, dtype="bf16", seed=T + h + d, device=DEV)
     _check_full(x, W, masks, _run(x, W, masks))
 
