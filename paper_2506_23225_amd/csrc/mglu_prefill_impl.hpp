@@ -27,6 +27,9 @@
 #include "mglu_common.hpp"
 #include "mglu_kernels.hpp"
 
+#ifndef MGLU_PREFILL_AD1
+#define MGLU_PREFILL_AD1 2   // tiles of W fetched ahead with one mask and in the two-matrix reference (two column blocks per wavefront)
+#endif
 #ifndef MGLU_PREFILL_AD_SMALL
 #define MGLU_PREFILL_AD_SMALL 6   // tiles of W fetched ahead in the 4-wavefront shapes that have the registers for it
 #endif
@@ -528,7 +531,7 @@ static hipError_t launch_prefill_masks(const PrefillParams &p, hipStream_t strea
 {
     // accumulators (1 + n_m sets of CB x TB x 4 registers) must fit 256 registers with the operands
     switch (round_up_masks(p.n_masks)) {
-    case 1: return launch_prefill_best<Tr, 1, MODE, Tile<2, 8, 8, 1>, Tile<2, 8, 4, MGLU_PREFILL_AD_SMALL>>(p, stream);
+    case 1: return launch_prefill_best<Tr, 1, MODE, Tile<2, 8, 8, MGLU_PREFILL_AD1>, Tile<2, 8, 4, MGLU_PREFILL_AD_SMALL>>(p, stream);
     case 2: return launch_prefill_best<Tr, 2, MODE, Tile<1, 8, 8, 2>, Tile<1, 8, 4, MGLU_PREFILL_AD_SMALL>>(p, stream);
     case 4: return launch_prefill_best<Tr, 4, MODE, Tile<1, 8, 8, 2>, Tile<1, 6, 8, 2>, Tile<1, 8, 4, 3>, Tile<1, 4, 4, MGLU_PREFILL_AD_SMALL>>(p, stream);
     case 8: return launch_prefill_best<Tr, 8, MODE, Tile<1, 4, 8, 2>, Tile<1, 4, 4, 3>>(p, stream);
@@ -539,7 +542,7 @@ static hipError_t launch_prefill_masks(const PrefillParams &p, hipStream_t strea
 template <typename Tr>
 static hipError_t launch_prefill_t(const PrefillParams &p, int mode, hipStream_t stream)
 {
-    if (mode == kModeSwiglu) return launch_prefill_one<Tr, 1, 2, 8, kModeSwiglu, 1, 8>(p, stream);
+    if (mode == kModeSwiglu) return launch_prefill_one<Tr, 1, 2, 8, kModeSwiglu, MGLU_PREFILL_AD1, 8>(p, stream);
     // plain projection (one accumulator set): 4 column blocks per wavefront on full launches -- twice the MFMAs
     // per loaded fragment, 51-53 % of peak instead of 40-43 % on the 14336 -> 4096 projection
     if (mode == kModeLinear)
