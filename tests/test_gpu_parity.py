@@ -91,6 +91,26 @@ def test_prefill_four_masks_tall_tile(dtype, T, h, d, n_m):
         _check_full(x, W, masks, out)
 
 
+def _random_shapes(n, seed):
+    rng = np.random.default_rng(seed)
+    shapes = []
+    for _ in range(n):
+        n_m = int(rng.choice([1, 2, 3, 4, 5, 8, 11, 16]))
+        T = int(rng.choice([rng.integers(1, 17), rng.integers(17, 65), rng.integers(65, 300)]))
+        h = 8 * int(rng.integers(2, 81))          # 16 .. 640, any multiple of 8
+        d = int(rng.integers(1, 600))
+        shapes.append((str(rng.choice(["bf16", "f16"])), T, h, d, n_m))
+    return shapes
+
+
+@pytest.mark.parametrize("dtype,T,h,d,n_m", _random_shapes(40, seed=2506))
+def test_random_shapes(dtype, T, h, d, n_m):
+    """Seeded random shapes across the hand-over points between the kernels and their tile shapes: any token
+    count up to 300, any d_model that is a multiple of 8, any d_ff, the mask counts of every instantiation."""
+    x, W, masks = synth.make_inputs(h, d, n_m, T, dtype=dtype, seed=T + h + d + n_m, device=DEV)
+    _check_full(x, W, masks, _run(x, W, masks))
+
+
 @pytest.mark.parametrize("T,h,d,n_m", [(40, 384, 25616, 2), (200, 520, 272, 4), (300, 384, 1000, 8), (129, 1024, 130, 1)])
 def test_fp16_panel_and_tiled_kernels(T, h, d, n_m):
     """fp16, the paper's own precision, through the panel kernel and the MFMA-tiled kernel."""
