@@ -172,7 +172,7 @@ def main():
     args = parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (the layer shards by d_ff "
-              "columns with no exchange; see DESIGN.md). Run with --gpus 1.", file=sys.stderr)
+              "columns with no exchange between the shards). Run with --gpus 1.", file=sys.stderr)
         sys.exit(2)
     import torch
     from paper_2506_23225_amd import _lib, api, synth
