@@ -6,8 +6,7 @@ import ctypes
 import os
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-# MGLU_LIBRARY_PATH selects another build of the same ABI (e.g. one compiled with other tuning macros).
-LIB_PATH = os.environ.get("MGLU_LIBRARY_PATH") or os.path.join(HERE, "libmglu.so")
+LIB_PATH = os.path.join(HERE, "libmglu.so")
 
 MGLU_OK = 0
 MGLU_F32, MGLU_BF16, MGLU_F16 = 0, 1, 2
@@ -54,15 +53,19 @@ SIGNATURES = {
 _lib = None
 
 
-def load():
-    """The loaded library, with argument types set.  Raises if libmglu.so is missing."""
+def load(path=None):
+    """The loaded library, with argument types set.  Raises if libmglu.so is missing.
+
+    `path` (first call only) loads another build of the same ABI instead, e.g. one compiled with
+    other tuning macros for an experiment; the product never passes it."""
     global _lib
     if _lib is None:
-        if not os.path.exists(LIB_PATH):
+        path = path or LIB_PATH
+        if not os.path.exists(path):
             raise RuntimeError(
                 "%s is missing: build it with `python -m paper_2506_23225_amd.build` "
-                "(there is no fallback path)" % LIB_PATH)
-        lib = ctypes.CDLL(LIB_PATH)
+                "(there is no fallback path)" % path)
+        lib = ctypes.CDLL(path)
         for name, (restype, argtypes) in SIGNATURES.items():
             fn = getattr(lib, name)
             fn.restype = restype

@@ -41,6 +41,33 @@ def _ptr(t, name):
     return t.data_ptr()
 
 
+_TORCH_OF = {v: k for k, v in _DTYPE.items()}
+
+
+def _expect(t, name, numel=None, dtype=None, min_bytes=None):
+    """Cheap host-side checks of a tensor against the descriptor: the kernels trust the sizes they are given."""
+    if t is None:
+        return
+    if dtype is not None and t.dtype != dtype:
+        raise ValueError("%s has dtype %s, the descriptor says %s" % (name, t.dtype, dtype))
+    if numel is not None and t.numel() != numel:
+        raise ValueError("%s has %d elements, the descriptor says %d" % (name, t.numel(), numel))
+    if min_bytes is not None and t.numel() * t.element_size() < min_bytes:
+        raise ValueError("%s holds %d bytes, %d are needed" % (name, t.numel() * t.element_size(), min_bytes))
+
+
+def _expect_layer(desc, x=None, out=None, W_packed=None, masks_packed=None, W=None, masks=None):
+    dt = _TORCH_OF[desc.dtype]
+    _expect(x, "x", desc.tokens * desc.d_model, dt)
+    _expect(out, "out", desc.tokens * desc.d_ff, dt)
+    _expect(W, "W", desc.d_model * desc.d_ff, dt)
+    _expect(masks, "masks", desc.n_masks * desc.d_model * desc.d_ff, torch.uint8)
+    if W_packed is not None:
+        _expect(W_packed, "W_packed", min_bytes=mglu_packed_weight_bytes(desc))
+    if masks_packed is not None:
+        _expect(masks_packed, "masks_packed", min_bytes=mglu_packed_mask_bytes(desc))
+
+
 def make_desc(tokens, d_model, d_ff, n_masks, dtype, w_layout="kn"):
     return MgluDesc(int(tokens), int(d_model), int(d_ff), int(n_masks), _DTYPE[dtype], _LAYOUT[w_layout])
 
@@ -67,8 +94,10 @@ def mglu_forward_bool_workspace_bytes(desc):
 
 def mglu_pack_weights(desc, W, packed=None):
     """W [d_model,d_ff] ('kn') or [d_ff,d_model] ('nk') -> packed uint8 buffer."""
+    _expect_layer(desc, W=W)
     if packed is None:
         packed = torch.empty(mglu_packed_weight_bytes(desc), dtype=torch.uint8, device=W.device)
+    _expect(packed, "packed", min_bytes=mglu_packed_weight_bytes(desc))
     _check(_lib.load().mglu_pack_weights(desc, _ptr(W, "W"), _ptr(packed, "packed"), _stream(W)))
     return packed
 
@@ -77,8 +106,10 @@ def mglu_pack_masks(desc, masks, packed=None):
     """masks uint8/bool [n_masks,d_model,d_ff] ('kn') or [n_masks,d_ff,d_model] ('nk') -> packed buffer."""
     if masks.dtype == torch.bool:
         masks = masks.view(torch.uint8)
+    _expect_layer(desc, masks=masks)
     if packed is None:
         packed = torch.empty(mglu_packed_mask_bytes(desc), dtype=torch.uint8, device=masks.device)
+    _expect(packed, "packed", min_bytes=mglu_packed_mask_bytes(desc))
     _check(_lib.load().mglu_pack_masks(desc, _ptr(masks, "masks"), _ptr(packed, "packed"), _stream(masks)))
     return packed
 
@@ -94,6 +125,7 @@ def mglu_forward(desc, x, W_packed, masks_packed, out=None, workspace=None):
     if out is None:
         out = torch.empty(desc.tokens, desc.d_ff, dtype=x.dtype, device=x.device)
     workspace, ws_bytes = _workspace(desc, x.device, workspace)
+    _expect_layer(desc, x=x, out=out, W_packed=W_packed, masks_packed=masks_packed)
     _check(_lib.load().mglu_forward(desc, _ptr(x, "x"), _ptr(W_packed, "W_packed"),
                                     _ptr(masks_packed, "masks_packed"), _ptr(out, "out"),
                                     _ptr(workspace, "workspace"), ws_bytes, _stream(x)))
@@ -116,6 +148,8 @@ def mglu_forward_variant(desc, x, W_packed, masks_packed, gate="swish", mask_use
         out = torch.empty(desc.tokens, desc.d_ff, dtype=x.dtype, device=x.device)
     workspace, ws_bytes = _workspace(desc, x.device, workspace)
     keep, ref = _variant(gate, mask_use, route_weights)
+    _expect_layer(desc, x=x, out=out, W_packed=W_packed, masks_packed=masks_packed)
+    _expect(route_weights, "route_weights", desc.tokens * desc.n_masks, torch.float32)
     _check(_lib.load().mglu_forward_variant(desc, ref, _ptr(x, "x"), _ptr(W_packed, "W_packed"),
                                             _ptr(masks_packed, "masks_packed"), _ptr(out, "out"),
                                             _ptr(workspace, "workspace"), ws_bytes, _stream(x)))
@@ -126,6 +160,9 @@ def mglu_route_topk(desc, x, Wr, k, weights=None):
     """Top-K router: softmax over the k largest logits of x Wr per token, 0 elsewhere; fp32 [T, n_masks]."""
     if weights is None:
         weights = torch.empty(desc.tokens, desc.n_masks, dtype=torch.float32, device=x.device)
+    _expect(x, "x", desc.tokens * desc.d_model, _TORCH_OF[desc.dtype])
+    _expect(Wr, "Wr", desc.d_model * desc.n_masks, _TORCH_OF[desc.dtype])
+    _expect(weights, "weights", desc.tokens * desc.n_masks, torch.float32)
     _check(_lib.load().mglu_route_topk(desc, _ptr(x, "x"), _ptr(Wr, "Wr"), int(k), _ptr(weights, "weights"),
                                        _stream(x)))
     return weights
@@ -136,6 +173,7 @@ def mglu_linear_forward(desc, a, W_packed, out=None, workspace=None):
     if out is None:
         out = torch.empty(desc.tokens, desc.d_ff, dtype=a.dtype, device=a.device)
     workspace, ws_bytes = _workspace(desc, a.device, workspace)
+    _expect_layer(desc, x=a, out=out, W_packed=W_packed)
     _check(_lib.load().mglu_linear_forward(desc, _ptr(a, "a"), _ptr(W_packed, "W_packed"), _ptr(out, "out"),
                                            _ptr(workspace, "workspace"), ws_bytes, _stream(a)))
     return out
@@ -150,6 +188,11 @@ def mglu_ffn_forward(desc, x, W_packed, masks_packed, Wo_packed, gate="swish", m
         y = torch.empty(desc.tokens, desc.d_model, dtype=x.dtype, device=x.device)
     workspace, ws_bytes = _workspace(desc, x.device, workspace)
     keep, ref = _variant(gate, mask_use, route_weights)
+    _expect_layer(desc, x=x, out=hidden, W_packed=W_packed, masks_packed=masks_packed)
+    _expect(y, "y", desc.tokens * desc.d_model, x.dtype)
+    down = MgluDesc(desc.tokens, desc.d_ff, desc.d_model, 1, desc.dtype, desc.w_layout)
+    _expect(Wo_packed, "Wo_packed", min_bytes=mglu_packed_weight_bytes(down))
+    _expect(route_weights, "route_weights", desc.tokens * desc.n_masks, torch.float32)
     _check(_lib.load().mglu_ffn_forward(desc, ref, _ptr(x, "x"), _ptr(W_packed, "W_packed"),
                                         _ptr(masks_packed, "masks_packed"), _ptr(Wo_packed, "Wo_packed"),
                                         _ptr(hidden, "hidden"), _ptr(y, "y"), _ptr(workspace, "workspace"),
@@ -164,6 +207,7 @@ def mglu_forward_bool(desc, x, W, masks, out=None, workspace=None):
         out = torch.empty(desc.tokens, desc.d_ff, dtype=x.dtype, device=x.device)
     if workspace is None:
         workspace = torch.zeros(mglu_forward_bool_workspace_bytes(desc), dtype=torch.uint8, device=x.device)
+    _expect_layer(desc, x=x, out=out, W=W, masks=masks)
     _check(_lib.load().mglu_forward_bool(desc, _ptr(x, "x"), _ptr(W, "W"), _ptr(masks, "masks"),
                                          _ptr(out, "out"), _ptr(workspace, "workspace"),
                                          workspace.numel(), _stream(x)))
@@ -177,6 +221,7 @@ def mglu_projections(desc, x, W_packed, masks_packed, workspace=None):
     gate = torch.empty(n, T, d, dtype=torch.float32, device=x.device)
     value = torch.empty(n, T, d, dtype=torch.float32, device=x.device)
     workspace, ws_bytes = _workspace(desc, x.device, workspace)
+    _expect_layer(desc, x=x, W_packed=W_packed, masks_packed=masks_packed)
     _check(_lib.load().mglu_projections(desc, _ptr(x, "x"), _ptr(W_packed, "W_packed"),
                                         _ptr(masks_packed, "masks_packed"), _ptr(t, "t"),
                                         _ptr(gate, "gate"), _ptr(value, "value"),
@@ -188,6 +233,8 @@ def swiglu_forward(desc, x, Wg_packed, Wv_packed, out=None, workspace=None):
     if out is None:
         out = torch.empty(desc.tokens, desc.d_ff, dtype=x.dtype, device=x.device)
     workspace, ws_bytes = _workspace(desc, x.device, workspace)
+    _expect_layer(desc, x=x, out=out, W_packed=Wg_packed)
+    _expect(Wv_packed, "Wv_packed", min_bytes=mglu_packed_weight_bytes(desc))
     _check(_lib.load().swiglu_forward(desc, _ptr(x, "x"), _ptr(Wg_packed, "Wg_packed"),
                                       _ptr(Wv_packed, "Wv_packed"), _ptr(out, "out"),
                                       _ptr(workspace, "workspace"), ws_bytes, _stream(x)))
