@@ -128,6 +128,23 @@ mglu_status mglu_forward_bool(const mglu_desc *desc, const void *x_dev, const vo
                               const uint8_t *masks_dev, void *out_dev,
                               void *workspace_dev, size_t workspace_bytes, void *stream);
 
+/* mglu_forward_bool for callers that cannot allocate device memory or hand over a workspace:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments, result and kernels as mglu_forward_bool, but the packed copies of W and the masks
+ * are staged in a device array that is part of the library itself (MGLU_STATIC_SCRATCH_BYTES,
+ * one copy on every GPU the library runs on, held until the process ends); the call allocates
+ * and frees nothing.
+ *   - Layers whose staging (mglu_forward_bool_workspace_bytes) exceeds MGLU_STATIC_SCRATCH_BYTES
+ *     are rejected with MGLU_ERR_WORKSPACE before anything is enqueued.
+ *   - Every call on a GPU uses that GPU's one array: calls that overlap on one GPU (two streams,
+ *     two threads) race on it.  Calls on one stream are ordered and safe; nothing of an earlier
+ *     call's contents is relied on (both packed buffers are fully rewritten each time).
+ *   - The first call on each device looks the array's address up once (no allocation; make that
+ *     first call outside a graph capture). */
+#define MGLU_STATIC_SCRATCH_BYTES (32u << 20)
+mglu_status mglu_forward_bool_static(const mglu_desc *desc, const void *x_dev, const void *W_dev,
+                                     const uint8_t *masks_dev, void *out_dev, void *stream);
+
 /* Debug view of Alg. 1's accumulator z: the raw projections before the activation, fp32.
  *   t_dev [tokens][d_ff] = x W;  gate_dev, value_dev [n_masks][tokens][d_ff].
  * Any of the three may be NULL.  Same packed inputs and workspace rules as mglu_forward. */

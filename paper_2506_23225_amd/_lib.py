@@ -39,6 +39,7 @@ SIGNATURES = {
     "mglu_forward": (ctypes.c_int, [_D, _P, _P, _P, _P, _P, _SZ, _P]),
     "mglu_forward_bool_workspace_bytes": (_SZ, [_D]),
     "mglu_forward_bool": (ctypes.c_int, [_D, _P, _P, _P, _P, _P, _SZ, _P]),
+    "mglu_forward_bool_static": (ctypes.c_int, [_D, _P, _P, _P, _P, _P]),
     "mglu_projections": (ctypes.c_int, [_D, _P, _P, _P, _P, _P, _P, _P, _SZ, _P]),
     "mglu_forward_variant": (ctypes.c_int, [_D, ctypes.POINTER(MgluVariant), _P, _P, _P, _P, _P, _SZ, _P]),
     "mglu_route_topk": (ctypes.c_int, [_D, _P, _P, ctypes.c_int, _P, _P]),

@@ -214,6 +214,16 @@ def mglu_forward_bool(desc, x, W, masks, out=None, workspace=None):
     return out
 
 
+def mglu_forward_bool_static(desc, x, W, masks, out):
+    """mglu_forward_bool staged in the library's own static device array; `out` is the caller's (nothing is allocated)."""
+    if masks.dtype == torch.bool:
+        masks = masks.view(torch.uint8)
+    _expect_layer(desc, x=x, out=out, W=W, masks=masks)
+    _check(_lib.load().mglu_forward_bool_static(desc, _ptr(x, "x"), _ptr(W, "W"), _ptr(masks, "masks"),
+                                                _ptr(out, "out"), _stream(x)))
+    return out
+
+
 def mglu_projections(desc, x, W_packed, masks_packed, workspace=None):
     """Returns (t [T,d], gate [n_masks,T,d], value [n_masks,T,d]) in fp32."""
     T, d, n = desc.tokens, desc.d_ff, desc.n_masks

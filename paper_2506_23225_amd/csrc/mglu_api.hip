@@ -7,6 +7,8 @@
 #include "mglu_common.hpp"
 #include "mglu_kernels.hpp"
 
+#include <mutex>
+
 namespace {
 
 thread_local char g_error[512] = "";
@@ -133,6 +135,43 @@ mglu::PackParams pack_params(const mglu_desc *d, const void *src, void *dst)
         mglu_status s_ = (expr);            \
         if (s_ != MGLU_OK) return s_;       \
     } while (0)
+
+
+mglu_status check_bool_inputs(const void *x_dev, const void *W_dev, const uint8_t *masks_dev, const void *out_dev)
+{
+    MGLU_TRY(check_ptr(x_dev, "x_dev"));
+    MGLU_TRY(check_ptr(W_dev, "W_dev"));
+    MGLU_TRY(check_ptr(masks_dev, "masks_dev"));
+    return check_ptr(out_dev, "out_dev");
+}
+
+// ---- device memory that belongs to the library: staging for mglu_forward_bool_static ----
+// One array per GPU (every device the code object is loaded on holds its own copy at its own
+// address, until the process ends).  In host code the array's name is only a handle for the
+// symbol look-up below; what kernels and the pack calls get is the device address it returns.
+__device__ __align__(256) unsigned char scratch[MGLU_STATIC_SCRATCH_BYTES];
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_lock;
+char *g_scratch_ptr[kMaxDevices] = {};
+
+// The current device's copy of the array; looked up once per device, with that device current.
+mglu_status static_scratch(char **out)
+{
+    int dev = -1;
+    MGLU_TRY(hip_result(hipGetDevice(&dev), "hipGetDevice"));
+    if (dev < 0 || dev >= kMaxDevices) return fail(MGLU_ERR_UNSUPPORTED, "device ordinal %d is beyond %d", dev, kMaxDevices);
+    std::lock_guard<std::mutex> guard(g_scratch_lock);
+    if (!g_scratch_ptr[dev]) {
+        void *ptr = nullptr;
+        MGLU_TRY(hip_result(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)), "hipGetSymbolAddress(scratch)"));
+        if (!ptr || (reinterpret_cast<uintptr_t>(ptr) & 255u))
+            return fail(MGLU_ERR_HIP, "the static scratch array has no usable device address");
+        g_scratch_ptr[dev] = static_cast<char *>(ptr);
+    }
+    *out = g_scratch_ptr[dev];
+    return MGLU_OK;
+}
 
 }  // namespace
 
@@ -308,6 +347,18 @@ mglu_status mglu_ffn_forward(const mglu_desc *desc, const mglu_variant *variant,
     return mglu_linear_forward(&down, hidden_dev, Wo_packed_dev, y_dev, workspace_dev, workspace_bytes, stream);
 }
 
+// Packs W and the masks into `ws` (arguments already checked, `ws` large enough), then runs the layer on them.
+static mglu_status pack_and_forward(const mglu_desc *desc, const void *x_dev, const void *W_dev,
+                                    const uint8_t *masks_dev, void *out_dev, char *ws, size_t ws_bytes, void *stream)
+{
+    void *wp = ws;
+    void *mp = ws + align_up(mglu_packed_weight_bytes(desc), 256);
+    char *fw = static_cast<char *>(mp) + align_up(mglu_packed_mask_bytes(desc), 256);
+    MGLU_TRY(mglu_pack_weights(desc, W_dev, wp, stream));
+    MGLU_TRY(mglu_pack_masks(desc, masks_dev, mp, stream));
+    return mglu_forward(desc, x_dev, wp, mp, out_dev, fw, ws_bytes - (size_t)(fw - ws), stream);
+}
+
 size_t mglu_forward_bool_workspace_bytes(const mglu_desc *desc)
 {
     const size_t w = mglu_packed_weight_bytes(desc), m = mglu_packed_mask_bytes(desc);
@@ -320,17 +371,29 @@ mglu_status mglu_forward_bool(const mglu_desc *desc, const void *x_dev, const vo
                               size_t workspace_bytes, void *stream)
 {
     MGLU_TRY(check_forward(desc, true));
+    MGLU_TRY(check_bool_inputs(x_dev, W_dev, masks_dev, out_dev));
     MGLU_TRY(check_ptr(workspace_dev, "workspace_dev"));
     const size_t need = mglu_forward_bool_workspace_bytes(desc);
     if (workspace_bytes < need)
         return fail(MGLU_ERR_WORKSPACE, "workspace has %zu bytes, mglu_forward_bool needs %zu", workspace_bytes, need);
-    char *ws = static_cast<char *>(workspace_dev);
-    void *wp = ws;
-    void *mp = ws + align_up(mglu_packed_weight_bytes(desc), 256);
-    char *fw = static_cast<char *>(mp) + align_up(mglu_packed_mask_bytes(desc), 256);
-    MGLU_TRY(mglu_pack_weights(desc, W_dev, wp, stream));
-    MGLU_TRY(mglu_pack_masks(desc, masks_dev, mp, stream));
-    return mglu_forward(desc, x_dev, wp, mp, out_dev, fw, workspace_bytes - (size_t)(fw - ws), stream);
+    return pack_and_forward(desc, x_dev, W_dev, masks_dev, out_dev, static_cast<char *>(workspace_dev),
+                            workspace_bytes, stream);
+}
+
+mglu_status mglu_forward_bool_static(const mglu_desc *desc, const void *x_dev, const void *W_dev,
+                                     const uint8_t *masks_dev, void *out_dev, void *stream)
+{
+    MGLU_TRY(check_forward(desc, true));
+    MGLU_TRY(check_bool_inputs(x_dev, W_dev, masks_dev, out_dev));
+    const size_t need = mglu_forward_bool_workspace_bytes(desc);
+    if (need > (size_t)MGLU_STATIC_SCRATCH_BYTES)
+        return fail(MGLU_ERR_WORKSPACE,
+                    "mglu_forward_bool_static: d_model=%d x d_ff=%d with %d masks needs %zu bytes of staging, the "
+                    "library's static scratch holds %zu; use mglu_forward_bool with a workspace of your own",
+                    desc->d_model, desc->d_ff, desc->n_masks, need, (size_t)MGLU_STATIC_SCRATCH_BYTES);
+    char *ws = nullptr;
+    MGLU_TRY(static_scratch(&ws));
+    return pack_and_forward(desc, x_dev, W_dev, masks_dev, out_dev, ws, (size_t)MGLU_STATIC_SCRATCH_BYTES, stream);
 }
 
 mglu_status mglu_projections(const mglu_desc *desc, const void *x_dev, const void *W_packed_dev,

@@ -57,6 +57,12 @@ def test_bad_arguments_are_reported_not_launched(lib):
         setattr(bad, field, value)
         assert fwd(bad) == code, (field, value, lib.mglu_last_error())
     assert lib.mglu_forward_bool(ok, fake, fake, fake, fake, fake, 16, None) == WORKSPACE
+    # the allocation-free variant refuses layers beyond its static staging array, and bad pointers, before any GPU call
+    big = _lib.MgluDesc(1, 4096, 14336, 8, _lib.MGLU_BF16, _lib.MGLU_W_KN)
+    assert lib.mglu_forward_bool_static(big, fake, fake, fake, fake, None) == WORKSPACE
+    assert b"static scratch" in lib.mglu_last_error()
+    assert lib.mglu_forward_bool_static(ok, fake, None, fake, fake, None) == INVALID
+    assert lib.mglu_forward_bool(ok, fake, fake, fake, None, fake, 1 << 30, None) == INVALID   # out checked before any launch
     assert lib.mglu_pack_masks(ok, None, fake, None) == INVALID
     assert lib.mglu_pack_weights(ok, fake, None, None) == INVALID
     assert lib.mglu_stream_read(fake, 24, fake, None) == INVALID
