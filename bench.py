@@ -3,15 +3,23 @@
 
 A step is one mglu_forward call (the whole hot path: stream W and the packed masks,
 accumulate, reduce, fused Swish/gate*value/mixture epilogue, store) on synthetic inputs
-already resident in HBM.  The headline workload is the decode GEMV configuration
-(d_model 2048, d_ff 5632, four masks, one token, bf16); every step reads a different copy
-of (W, masks) out of a ring larger than the 256 MB last-level cache, so the rate is an HBM
-rate, not a cache rate.  One JSON line is printed; the other configurations ride along
-under "extra".
+already resident in HBM.  The headline workload is the largest single-GPU decode
+configuration (d_model 8192, d_ff 28672, eight masks, one token, bf16); every step reads a
+different copy of (W, masks) out of a ring larger than the 256 MB last-level cache, so the
+rate is an HBM rate, not a cache rate.  One JSON line is printed; the other configurations
+ride along under "extra", each with the step counts it was timed with.
+
+Timing method (every row): W warm-up steps, then an untimed settle phase (more of the same
+steps until the GPU has been busy for ~30 ms, so that the shader clock has settled), then a
+blocker (a few launches of the library's plain read kernel) behind which the K timed steps
+are queued, so that they run back to back on the device whatever the host's launch rate;
+HIP events on the launch stream bracket exactly the K steps, with a synchronisation on both
+sides.
 """
 import argparse
 import json
 import os
+import subprocess
 import sys
 import time
 
@@ -22,18 +30,21 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0        # MI355X HBM3E, published
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16, published
 LLC_BYTES = 256 * 2 ** 20    # last-level (Infinity) cache
-HEADLINE = "decode_gemv 2048x5632 n_m=4 T=1"
+HEADLINE = "large 8192x28672 n_m=8 T=1"
+HEADLINE_KERNEL = "mglu::stream_resident_kernel<mglu::Bf16Traits, 8, 0, 2, false>"
+HEADLINE_TRAFFIC_KEY = "large_nm8_T1"
+SETTLE_MS = 30.0
 
 
 def parse_args():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=5000)
-    ap.add_argument("--warmup", type=int, default=1000)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=50)
     ap.add_argument("--no-extra", action="store_true", help="headline workload only")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     ap.add_argument("--no-refs", action="store_true",
-                    help="skip the warm-cache, SwiGLU-reference and read-ceiling legs of the headline")
+                    help="skip the SwiGLU-reference and read-ceiling legs of the headline")
     ap.add_argument("--probe", default="",
                     help="profiling aid: launch only this workload ('headline' or a substring of an extra "
                          "workload's name) 20 times, then one mglu_stream_read and one device copy of "
@@ -45,7 +56,7 @@ def parse_args():
 class Workload:
     """One (config, tokens) case with a ring of packed (W, masks) copies on the GPU."""
 
-    def __init__(self, name, cfg, ring_bytes=2 * LLC_BYTES, swiglu=True, max_ring=64):
+    def __init__(self, name, cfg, ring_bytes=2 * LLC_BYTES, swiglu=True, max_ring=64, keep_inputs=False):
         import torch
         from paper_2506_23225_amd import api, costmodel, synth
         self.name, self.cfg = name, cfg
@@ -53,10 +64,12 @@ class Workload:
         T, h, d, n_m = cfg["tokens"], cfg["d_model"], cfg["d_ff"], cfg["n_masks"]
         dt = synth.TORCH_DTYPE[cfg["dtype"]]
         self.desc = api.make_desc(T, h, d, n_m, dt)
+        self.plan = api.mglu_describe_plan(self.desc)
         x, W, masks = synth.make_inputs(**cfg, seed=0, device="cuda:0")
         self.x = x
         Wp = api.mglu_pack_weights(self.desc, W)
         Mp = api.mglu_pack_masks(self.desc, masks)
+        self.inputs = (x, W, masks) if keep_inputs else None   # for the CPU-oracle leg
         del masks
         per_copy = Wp.numel() + Mp.numel()
         self.copies = max(1, min(max_ring, -(-ring_bytes // per_copy)))
@@ -115,28 +128,75 @@ class Workload:
         self.api.swiglu_forward(self.desc, self.x, Wg, Wv, out=self.out, workspace=self.ws)
 
 
-def time_steps(torch, fn, steps, warmup):
-    """ms per step over exactly `steps` calls, HIP events on the launch stream, synchronised on both sides."""
-    for i in range(warmup):
-        fn(i)
-    torch.cuda.synchronize()
-    start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    t0 = time.perf_counter()
-    start.record()
-    for i in range(steps):
-        fn(warmup + i)
-    stop.record()
-    torch.cuda.synchronize()
-    wall_ms = (time.perf_counter() - t0) * 1e3
-    return start.elapsed_time(stop) / steps, wall_ms / steps
+class Timer:
+    """HIP-event timing of exactly K steps that run back to back on the device (see the module docstring)."""
+
+    def __init__(self, torch, api):
+        self.torch, self.api = torch, api
+        self.block_buf = torch.empty(2 ** 30, dtype=torch.uint8, device="cuda:0").random_(0, 255)
+        self.sink = torch.zeros(256, dtype=torch.int32, device="cuda:0")
+        self.block_ms = None      # duration of one blocker launch, measured once
+
+    def _blocker(self, n):
+        for _ in range(n):
+            self.api.mglu_stream_read(self.block_buf, self.sink)
+
+    def run(self, fn, steps, warmup):
+        """-> dict(ms, wall_ms, steps, warmup, settle_steps, blocker_launches)."""
+        torch = self.torch
+        if self.block_ms is None:
+            self._blocker(2)
+            torch.cuda.synchronize()
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            self._blocker(4)
+            b.record()
+            torch.cuda.synchronize()
+            self.block_ms = a.elapsed_time(b) / 4
+        # warm-up: W steps as asked, timed on the host side to learn the enqueue cost of one step
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(warmup):
+            fn(i)
+        # enqueue cost only (nothing synchronises inside the loop); too few steps to tell: assume a slow host
+        host_ms = (time.perf_counter() - t0) * 1e3 / warmup if warmup >= 3 else 0.03
+        torch.cuda.synchronize()
+        # settle: untimed steps until ~SETTLE_MS of GPU work has gone by since the warm-up began
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        fn(warmup)
+        b.record()
+        torch.cuda.synchronize()
+        one_ms = max(a.elapsed_time(b), 1e-3)
+        settle = int(min(2000, max(0, SETTLE_MS / one_ms - warmup)))
+        for i in range(settle):
+            fn(warmup + 1 + i)
+        base = warmup + 1 + settle
+        # blocker long enough for the host to enqueue all K steps behind it
+        host_ms = max(host_ms, 0.004)
+        n_block = int(min(4000, steps * host_ms * 1.5 / self.block_ms + 2))
+        start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        t0 = time.perf_counter()
+        self._blocker(n_block)
+        start.record()
+        for i in range(steps):
+            fn(base + i)
+        stop.record()
+        enqueue_ms = (time.perf_counter() - t0) * 1e3
+        torch.cuda.synchronize()
+        wall_ms = (time.perf_counter() - t0) * 1e3
+        return {"ms": start.elapsed_time(stop) / steps, "wall_ms": wall_ms / steps, "steps": steps, "warmup": warmup,
+                "settle_steps": settle + 1, "blocker_launches": n_block,
+                "host_enqueue_ms_per_step": enqueue_ms / (steps + n_block)}
 
 
-def summarize(w, ms, wall_ms, bound):
+def summarize(w, t, bound):
     T = w.cfg["tokens"]
+    ms = t["ms"]
     rec = {
-        "workload": w.name, "tokens": T, "d_model": w.cfg["d_model"], "d_ff": w.cfg["d_ff"],
+        "workload": w.name, "kernel": w.plan, "tokens": T, "d_model": w.cfg["d_model"], "d_ff": w.cfg["d_ff"],
         "n_masks": w.cfg["n_masks"], "dtype": w.cfg["dtype"], "ring_copies": w.copies,
-        "ms": ms, "wall_ms": wall_ms,
+        "ms": ms, "steps": t["steps"], "warmup": t["warmup"], "settle_steps": t["settle_steps"],
         "GBps": w.bytes / ms / 1e6, "hbm_frac": w.bytes / ms / 1e6 / HBM_PEAK_GBS,
         "TFLOPs": w.flops / ms / 1e9, "mfma_frac": w.flops / ms / 1e9 / MFMA_BF16_PEAK_TFLOPS,
         "tokens_per_s": T / ms * 1e3, "bound": bound,
@@ -144,28 +204,60 @@ def summarize(w, ms, wall_ms, bound):
     return rec
 
 
-def cpu_baseline(cfg, unit_bytes, budget_s=10.0):
-    """The fp64 oracle, as it stands, on the host cores: full decode-GEMV workload, repeated within a time budget."""
-    import numpy as np
+ONE_THREAD_C2 = r"""
+import sys, time
+sys.path.insert(0, %r)
+from oracle import mglu_oracle as oracle
+from paper_2506_23225_amd import synth
+cfg = synth.config("decode_gemv")
+x, W, masks = synth.make_inputs(**cfg, seed=0, device="cpu")
+xn, Wn, Mn = x.double().numpy(), W.double().numpy(), masks.numpy()
+oracle.mglu_forward(xn[:, :64], Wn[:64, :64], Mn[:, :64, :64])
+best = 1e9
+for _ in range(3):
+    t0 = time.perf_counter(); oracle.mglu_forward(xn, Wn, Mn); best = min(best, time.perf_counter() - t0)
+print(oracle.threads(), best)
+"""
+
+
+def cpu_baseline(head, budget_s=12.0, sample_cols=4096):
+    """The fp64 oracle, as it stands, on the host cores, on a bounded sample of the headline workload: the
+    first `sample_cols` output columns (all of d_model, all masks, the one token), repeated within a time budget."""
     from oracle import mglu_oracle as oracle
-    from paper_2506_23225_amd import synth
-    x, W, masks = synth.make_inputs(**cfg, seed=0, device="cpu")
-    xn, Wn, Mn = x.double().numpy(), W.double().numpy(), masks.numpy()
+    from paper_2506_23225_amd import costmodel
+    x, W, masks = head.inputs
+    cfg = head.cfg
+    xn = x.double().cpu().numpy()
+    Wn = W[:, :sample_cols].double().cpu().numpy()
+    Mn = masks[:, :, :sample_cols].cpu().numpy()
     oracle.mglu_forward(xn[:, :64], Wn[:64, :64], Mn[:, :64, :64])  # load the library
     times = []
     t_start = time.perf_counter()
-    while len(times) < 200 and (time.perf_counter() - t_start) < budget_s:
+    while len(times) < 100 and (time.perf_counter() - t_start) < budget_s:
         t0 = time.perf_counter()
         oracle.mglu_forward(xn, Wn, Mn)
         times.append(time.perf_counter() - t0)
     best = min(times)
-    return {
-        "value": unit_bytes / best / 1e9, "unit": "GB/s", "cores": oracle.threads(), "kind": "oracle",
-        "sample": "full %s workload (%d token, all %d columns), best of %d runs in %.1f s, %.3f s per run (median %.3f s)"
-                  % (cfg["name"], cfg["tokens"], cfg["d_ff"], len(times), time.perf_counter() - t_start, best,
-                     sorted(times)[len(times) // 2]),
-        "tokens_per_s": cfg["tokens"] / best,
+    frac = sample_cols / cfg["d_ff"]
+    sample_bytes = costmodel.mglu_bytes(cfg["d_model"], sample_cols, cfg["n_masks"], cfg["tokens"], cfg["dtype"])
+    rec = {
+        "value": sample_bytes / best / 1e9, "unit": "GB/s", "cores": oracle.threads(), "kind": "oracle",
+        "sample": "%s: the first %d of %d output columns (%.4f of the layer; every k, every mask, the one token), "
+                  "best of %d runs in %.1f s, %.3f s per run (median %.3f s); extrapolated full layer %.2f s"
+                  % (head.name, sample_cols, cfg["d_ff"], frac, len(times), time.perf_counter() - t_start, best,
+                     sorted(times)[len(times) // 2], best / frac),
+        "tokens_per_s": cfg["tokens"] / (best / frac),
     }
+    # one-thread time of the oracle on the decode GEMV configuration (2048 x 5632, 4 masks), in a process of its own
+    try:
+        env = dict(os.environ, OMP_NUM_THREADS="1")
+        out = subprocess.run([sys.executable, "-c", ONE_THREAD_C2 % ROOT], env=env, capture_output=True, text=True,
+                             timeout=120).stdout.split()
+        rec["decode_gemv_one_thread"] = {"threads": int(out[0]), "seconds": float(out[1]),
+                                         "note": "full decode_gemv workload, best of 3"}
+    except Exception as e:   # the baseline leg must not take the bench line down
+        rec["decode_gemv_one_thread"] = {"error": repr(e)}
+    return rec
 
 
 def main():
@@ -182,76 +274,55 @@ def main():
 
     if args.probe:
         return probe(torch, synth, args)
+    timer = Timer(torch, api)
 
-    # ---- headline: decode GEMV, cold ring ----
-    head_cfg = synth.config("decode_gemv")
-    head = Workload(HEADLINE, head_cfg, swiglu=not args.no_refs)
-    ms, wall_ms = time_steps(torch, head.step, args.steps, args.warmup)
-    rec = summarize(head, ms, wall_ms, "hbm")
+    # ---- headline: the largest decode configuration, cold ring ----
+    head_cfg = synth.config("large", n_masks=8, tokens=1)
+    head = Workload(HEADLINE, head_cfg, swiglu=not args.no_refs, keep_inputs=not args.no_cpu)
+    t = timer.run(head.step, args.steps, args.warmup)
+    rec = summarize(head, t, "hbm")
+    ms = t["ms"]
 
     result = {
         "metric": "MGLU decode HBM GB/s (frac of peak) + prefill TFLOP/s, tokens/s per layer",
         "value": rec["GBps"], "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": HEADLINE, "d_model": 2048, "d_ff": 5632, "n_masks": 4, "tokens": 1,
+        "config": {"workload": HEADLINE, "d_model": 8192, "d_ff": 28672, "n_masks": 8, "tokens": 1,
                    "ring_copies": head.copies, "cache": "cold (ring of copies > 2x last-level cache)"},
+        "timing": {"method": "HIP events around exactly `steps` launches queued behind a blocker launch, after "
+                             "`warmup` steps and an untimed settle phase",
+                   "settle_steps": t["settle_steps"], "blocker_launches": t["blocker_launches"],
+                   "host_enqueue_ms_per_step": t["host_enqueue_ms_per_step"], "wall_ms_per_step": t["wall_ms"]},
         "tokens_per_s": rec["tokens_per_s"], "hbm_frac": rec["hbm_frac"],
-        "wall_ms_per_step": wall_ms,
         "roofline": {"bound": "hbm", "achieved": rec["GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": rec["hbm_frac"], "traffic": measured_traffic("decode_gemv"),
-                     "kernel": "mglu::stream_resident_kernel<mglu::Bf16Traits, 4, 0, 2, true>",
+                     "frac": rec["hbm_frac"], "traffic": measured_traffic(HEADLINE_TRAFFIC_KEY),
+                     "traffic_source": "profiles/traffic.txt: committed rocprofv3 --pmc FETCH_SIZE + WRITE_SIZE "
+                                       "summary of this workload, a constant, not measured in this run",
+                     "kernel": HEADLINE_KERNEL, "kernel_from_plan_query": head.plan,
                      "bytes_per_launch": head.bytes},
     }
     if not args.no_refs:
-        sw_ms, _ = time_steps(torch, head.swiglu_step, args.steps, args.warmup)
-        warm = Workload("decode_gemv warm", head_cfg, ring_bytes=1, swiglu=False)
-        warm_ms, _ = time_steps(torch, warm.step, args.steps, args.warmup)
-        del warm
-        # measured streaming-read ceiling of this GPU (same load pattern, nothing else)
-        buf = torch.empty(2 ** 30, dtype=torch.uint8, device="cuda:0").random_(0, 255)
-        sink = torch.zeros(256, dtype=torch.int32, device="cuda:0")
-        read_ms, _ = time_steps(torch, lambda i: api.mglu_stream_read(buf, sink), 50, 5)
-        del buf
-        # the same number of bytes as one headline step, read cold by the plain read kernel: what a
-        # launch that only streams them costs on this GPU (start-up and drain included)
-        n_small = head.bytes // 16 * 16
-        smalls = [torch.empty(n_small, dtype=torch.uint8, device="cuda:0").random_(0, 255)
-                  for _ in range(max(2, int(2 * LLC_BYTES // n_small) + 1))]
-        small_ms, _ = time_steps(torch, lambda i: api.mglu_stream_read(smalls[i % len(smalls)], sink),
-                                 args.steps, args.warmup)
-        del smalls
-        result["plain_read_same_bytes"] = {"ms": small_ms, "GBps": n_small / small_ms / 1e6,
-                                           "note": "events around back-to-back launches; at this size the "
-                                                   "host's launch rate and the kernel time are about equal"}
-        # the same cold-ring steps captured once into a HIP graph and replayed: launch gaps of the host gone
-        gsteps = 4 * head.copies
-        cap = torch.cuda.Stream()
-        cap.wait_stream(torch.cuda.current_stream())
-        graph = torch.cuda.CUDAGraph()
-        with torch.cuda.stream(cap):
-            head.step(0)
-            cap.synchronize()
-            with torch.cuda.graph(graph, stream=cap):
-                for i in range(gsteps):
-                    head.step(i)
-        torch.cuda.current_stream().wait_stream(cap)
-        graph_ms, _ = time_steps(torch, lambda i: graph.replay(), 20, 3)
-        result["graph_replay"] = {"ms_per_step": graph_ms / gsteps, "GBps": head.bytes / (graph_ms / gsteps) / 1e6,
-                                  "steps_per_graph": gsteps}
-        del graph
-        result["warm_cache"] = {"ms": warm_ms, "GBps": head.bytes / warm_ms / 1e6}
-        result["swiglu_reference"] = {"ms": sw_ms, "GBps": head.glu_bytes / sw_ms / 1e6,
-                                      "mglu_over_swiglu_time": ms / sw_ms,
+        sw = timer.run(head.swiglu_step, args.steps, args.warmup)
+        # measured streaming-read ceiling of this GPU (same load pattern, nothing else), 1 GiB
+        rd = timer.run(lambda i: api.mglu_stream_read(timer.block_buf, timer.sink), 50, 5)
+        result["swiglu_reference"] = {"ms": sw["ms"], "GBps": head.glu_bytes / sw["ms"] / 1e6,
+                                      "mglu_over_swiglu_time": ms / sw["ms"],
                                       "byte_model_ratio": (16 + head_cfg["n_masks"]) / 32.0}
-        result["measured_read_ceiling_GBps"] = 2 ** 30 / read_ms / 1e6
+        result["measured_read_ceiling_GBps"] = 2 ** 30 / rd["ms"] / 1e6
+    if not args.no_cpu:
+        result["cpu_baseline"] = cpu_baseline(head)
+        result["gpu_over_cpu"] = result["value"] / result["cpu_baseline"]["value"]
     del head
+    torch.cuda.empty_cache()
 
     if not args.no_extra:
-        result["extra"] = run_extras(torch, synth, args)
-    if not args.no_cpu:
-        result["cpu_baseline"] = cpu_baseline(head_cfg, rec_bytes(head_cfg))
-        result["gpu_over_cpu"] = result["value"] / result["cpu_baseline"]["value"]
+        result["extra"] = run_extras(torch, synth, args, timer)
+        for e in result["extra"]:
+            if e["workload"].startswith("prefill_8b 4096x14336 n_m=4"):
+                result["prefill_TFLOPs"] = e["TFLOPs"]
+                result["prefill_mfma_frac"] = e["mfma_frac"]
+                result["prefill_tokens_per_s"] = e["tokens_per_s"]
     print(json.dumps(result))
 
 
@@ -269,23 +340,26 @@ def measured_traffic(key):
 
 
 def extra_cases(synth):
-    cases = []
+    """(name, config, bound, steps, warmup): every row is timed with its own counts, recorded in its record."""
+    cases = [("decode_gemv 2048x5632 n_m=4 T=1", synth.config("decode_gemv"), "hbm", 1000, 200)]
     for T in (1, 4, 16):
-        cases.append(("decode_8b 4096x14336 n_m=8 T=%d" % T, synth.config("decode_8b", tokens=T), "hbm", 400, 200))
+        cases.append(("decode_8b 4096x14336 n_m=8 T=%d" % T, synth.config("decode_8b", tokens=T), "hbm", 400, 100))
     for n_m in (1, 2, 4, 8):
         for T in (1, 32):
+            if (n_m, T) == (8, 1):
+                continue   # the headline
             cases.append(("large 8192x28672 n_m=%d T=%d" % (n_m, T),
-                          synth.config("large", n_masks=n_m, tokens=T), "hbm", 100, 60))
+                          synth.config("large", n_masks=n_m, tokens=T), "hbm", 100, 30))
     # the paper's own precision on the shape of its kernel timings (4096 x 14336, 4 masks, batch 1), and its prefill twin
-    cases.append(("fp16 4096x14336 n_m=4 T=1", synth.config("prefill_8b", tokens=1, dtype="f16"), "hbm", 400, 200))
-    cases.append(("prefill_8b 4096x14336 n_m=4 T=4096", synth.config("prefill_8b"), "mfma", 20, 20))
-    cases.append(("fp16 4096x14336 n_m=4 T=4096", synth.config("prefill_8b", dtype="f16"), "mfma", 20, 20))
+    cases.append(("fp16 4096x14336 n_m=4 T=1", synth.config("prefill_8b", tokens=1, dtype="f16"), "hbm", 400, 100))
+    cases.append(("prefill_8b 4096x14336 n_m=4 T=4096", synth.config("prefill_8b"), "mfma", 20, 10))
+    cases.append(("fp16 4096x14336 n_m=4 T=4096", synth.config("prefill_8b", dtype="f16"), "mfma", 20, 10))
     # 16 masks, the paper's largest ablation
-    cases.append(("decode_8b 4096x14336 n_m=16 T=1", synth.config("decode_8b", n_masks=16, tokens=1), "hbm", 300, 150))
-    cases.append(("prefill_8b 4096x14336 n_m=16 T=4096", synth.config("prefill_8b", n_masks=16), "mfma", 8, 8))
+    cases.append(("decode_8b 4096x14336 n_m=16 T=1", synth.config("decode_8b", n_masks=16, tokens=1), "hbm", 300, 100))
+    cases.append(("prefill_8b 4096x14336 n_m=16 T=4096", synth.config("prefill_8b", n_masks=16), "mfma", 8, 4))
     for n_m in (1, 2, 4, 8):
         cases.append(("large 8192x28672 n_m=%d T=2048" % n_m,
-                      synth.config("large", n_masks=n_m, tokens=2048), "mfma", 10, 10))
+                      synth.config("large", n_masks=n_m, tokens=2048), "mfma", 10, 5))
     return cases
 
 
@@ -294,7 +368,7 @@ def probe(torch, synth, args):
     the library's streaming read, which issues the same 16-byte-per-lane loads as the MGLU kernels
     (read counters), and a plain device copy (write counters)."""
     if args.probe == "headline":
-        name, cfg = HEADLINE, synth.config("decode_gemv")
+        name, cfg = HEADLINE, synth.config("large", n_masks=8, tokens=1)
     else:
         name, cfg = next((n, c) for n, c, _, _, _ in extra_cases(synth) if args.probe in n)
     w = Workload(name, cfg, swiglu=False)
@@ -310,12 +384,7 @@ def probe(torch, synth, args):
     torch.cuda.synchronize()
 
 
-def rec_bytes(cfg):
-    from paper_2506_23225_amd import costmodel
-    return costmodel.mglu_bytes(cfg["d_model"], cfg["d_ff"], cfg["n_masks"], cfg["tokens"], cfg["dtype"])
-
-
-def run_extras(torch, synth, args):
+def run_extras(torch, synth, args, timer):
     cases = extra_cases(synth)
     only = [s.strip() for s in args.only.split(",") if s.strip()]
     out = []
@@ -323,48 +392,49 @@ def run_extras(torch, synth, args):
         if only and not any(o in name for o in only):
             continue
         w = Workload(name, cfg)
-        ms, wall_ms = time_steps(torch, w.step, steps, warmup)
-        rec = summarize(w, ms, wall_ms, bound)
-        sw_ms, _ = time_steps(torch, w.swiglu_step, steps, warmup)
-        rec["swiglu_ms"] = sw_ms
-        rec["swiglu_GBps"] = w.glu_bytes / sw_ms / 1e6
-        rec["swiglu_TFLOPs"] = w.glu_flops / sw_ms / 1e9
-        rec["mglu_over_swiglu_time"] = ms / sw_ms
+        t = timer.run(w.step, steps, warmup)
+        rec = summarize(w, t, bound)
+        sw = timer.run(w.swiglu_step, steps, warmup)
+        rec["swiglu_ms"] = sw["ms"]
+        rec["swiglu_GBps"] = w.glu_bytes / sw["ms"] / 1e6
+        rec["swiglu_TFLOPs"] = w.glu_flops / sw["ms"] / 1e9
+        rec["mglu_over_swiglu_time"] = t["ms"] / sw["ms"]
         out.append(rec)
         print("[bench] %-40s %9.4f ms  %8.1f GB/s (%.1f%% HBM)  %8.1f TFLOP/s (%.1f%% MFMA)  swiglu %9.4f ms"
-              % (name, ms, rec["GBps"], 100 * rec["hbm_frac"], rec["TFLOPs"], 100 * rec["mfma_frac"], sw_ms),
+              % (name, t["ms"], rec["GBps"], 100 * rec["hbm_frac"], rec["TFLOPs"], 100 * rec["mfma_frac"], sw["ms"]),
               file=sys.stderr, flush=True)
         del w
         torch.cuda.empty_cache()
-    out.extend(run_widened(torch, synth, only))
+    out.extend(run_widened(torch, synth, only, timer))
     return out
 
 
-def run_widened(torch, synth, only):
+def run_widened(torch, synth, only, timer):
     """Rows beyond the up-projection itself: the Top-K routed layer and the whole FFN block."""
     out = []
-    cases = [("routed top-2 of 8, decode_8b 4096x14336 T=1", synth.config("decode_8b", tokens=1), "routed", 400, 200),
-             ("routed top-2 of 8, large 8192x28672 T=1", synth.config("large", n_masks=8, tokens=1), "routed", 100, 60),
-             ("ffn (layer + output projection), decode_8b 4096x14336 n_m=8 T=1", synth.config("decode_8b", tokens=1), "ffn", 400, 200),
-             ("ffn (layer + output projection), prefill_8b 4096x14336 n_m=4 T=4096", synth.config("prefill_8b"), "ffn", 20, 20)]
+    cases = [("routed top-2 of 8, decode_8b 4096x14336 T=1", synth.config("decode_8b", tokens=1), "routed", 400, 100),
+             ("routed top-2 of 8, large 8192x28672 T=1", synth.config("large", n_masks=8, tokens=1), "routed", 100, 30),
+             ("ffn (layer + output projection), decode_8b 4096x14336 n_m=8 T=1", synth.config("decode_8b", tokens=1), "ffn", 400, 100),
+             ("ffn (layer + output projection), prefill_8b 4096x14336 n_m=4 T=4096", synth.config("prefill_8b"), "ffn", 20, 10)]
     for name, cfg, kind, steps, warmup in cases:
         if only and not any(o in name for o in only):
             continue
         w = Workload(name, cfg, swiglu=False)
         if kind == "routed":
             w.enable_routing(2)
-            ms, wall_ms = time_steps(torch, w.routed_step, steps, warmup)
-            rec = summarize(w, ms, wall_ms, "hbm")
-            rec["note"] = "same bytes as the unrouted layer; sums of the unselected masks are skipped"
+            t = timer.run(w.routed_step, steps, warmup)
+            rec = summarize(w, t, "hbm")
+            rec["kernel"] = w.api.mglu_describe_plan(w.desc, "forward_variant")
         else:
             w.enable_ffn()
-            ms, wall_ms = time_steps(torch, w.ffn_step, steps, warmup)
+            t = timer.run(w.ffn_step, steps, warmup)
             w.bytes, w.flops = w.ffn_bytes, w.ffn_flops
-            rec = summarize(w, ms, wall_ms, "hbm" if cfg["tokens"] <= 64 else "mfma")
+            rec = summarize(w, t, "hbm" if cfg["tokens"] <= 64 else "mfma")
+            rec["kernel"] = w.plan + " + " + w.api.mglu_describe_plan(w.down, "linear")
             rec["note"] = "two launches; bytes and FLOPs include the output projection"
         out.append(rec)
         print("[bench] %-62s %9.4f ms  %8.1f GB/s (%.1f%% HBM)  %8.1f TFLOP/s (%.1f%% MFMA)"
-              % (name, ms, rec["GBps"], 100 * rec["hbm_frac"], rec["TFLOPs"], 100 * rec["mfma_frac"]),
+              % (name, t["ms"], rec["GBps"], 100 * rec["hbm_frac"], rec["TFLOPs"], 100 * rec["mfma_frac"]),
               file=sys.stderr, flush=True)
         del w
         torch.cuda.empty_cache()

@@ -226,6 +226,25 @@ mglu_status swiglu_forward(const mglu_desc *desc, const void *x_dev, const void 
  * cannot be dropped.  Gives the read bandwidth this GPU actually reaches. */
 mglu_status mglu_stream_read(const void *buf_dev, size_t bytes, uint32_t *sink_dev, void *stream);
 
+/* ---- which kernel a call would run (host only; for tests and reports) ----------------------- */
+
+/* The entry point being asked about. */
+typedef enum {
+    MGLU_CALL_FORWARD = 0,          /* mglu_forward, mglu_forward_bool */
+    MGLU_CALL_FORWARD_VARIANT = 1,  /* mglu_forward_variant with any variation switched on */
+    MGLU_CALL_PROJECTIONS = 2,      /* mglu_projections */
+    MGLU_CALL_LINEAR = 3,           /* mglu_linear_forward */
+    MGLU_CALL_SWIGLU = 4            /* swiglu_forward */
+} mglu_call;
+
+/* Writes into buf (len bytes, always NUL-terminated) the name of the kernel instantiation that
+ * `call` would launch for this descriptor -- kernel family and template arguments as in the
+ * library's symbol table, e.g. "stream_resident_kernel<Bf16Traits, 8, 0, 2, false>" -- without
+ * launching anything or touching a GPU.  The same checks as the call itself apply to the
+ * descriptor.  Lets a test suite assert which code path a shape exercises, and that every
+ * instantiation the library can select is covered by a parity test. */
+mglu_status mglu_describe_plan(const mglu_desc *desc, mglu_call call, char *buf, size_t len);
+
 /* ---- errors -------------------------------------------------------------------------------- */
 const char *mglu_last_error(void);              /* thread-local, never NULL */
 const char *mglu_status_string(mglu_status s);  /* static text for a code */

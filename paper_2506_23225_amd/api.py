@@ -251,6 +251,13 @@ def swiglu_forward(desc, x, Wg_packed, Wv_packed, out=None, workspace=None):
     return out
 
 
+def mglu_describe_plan(desc, call="forward"):
+    """Name of the kernel instantiation `call` would launch for this descriptor (host only, no GPU needed)."""
+    buf = ctypes.create_string_buffer(256)
+    _check(_lib.load().mglu_describe_plan(desc, _lib.MGLU_CALL[call], buf, len(buf)))
+    return buf.value.decode()
+
+
 def mglu_stream_read(buf, sink):
     _check(_lib.load().mglu_stream_read(_ptr(buf, "buf"), buf.numel() * buf.element_size(),
                                         _ptr(sink, "sink"), _stream(buf)))

@@ -137,6 +137,37 @@ mglu::PackParams pack_params(const mglu_desc *d, const void *src, void *dst)
     } while (0)
 
 
+// Everything a launch reads and writes besides the descriptor; unused members stay null / 0.
+struct Operands {
+    const void *x, *w, *w2;
+    const uint32_t *m;
+    void *out;
+    float *proj_t, *proj_gate, *proj_value;
+    int gate_fn, mask_use;
+    const float *route;
+};
+
+// The one place that picks the kernel family for a call: `mode` is a mglu::Mode.  With `describe` set
+// nothing is launched and the chosen kernel instantiation is written there instead.
+mglu_status run_layer(const mglu_desc *d, int mode, const Operands &o, void *stream, const char *what,
+                      char *describe = nullptr, size_t describe_len = 0)
+{
+    const int n_masks = (mode == mglu::kModeLinear || mode == mglu::kModeSwiglu) ? 1 : d->n_masks;
+    if (mode != mglu::kModeProjections && use_tiled_kernel(d, n_masks)) {
+        mglu::PrefillParams pp = prefill_params(d);
+        pp.x = o.x; pp.w = o.w; pp.w2 = o.w2; pp.m = o.m; pp.out = o.out;
+        pp.gate_fn = o.gate_fn; pp.mask_use = o.mask_use; pp.route = o.route;
+        pp.describe = describe; pp.describe_len = describe_len;
+        return hip_result(mglu::launch_prefill(pp, elem_of(d), mode, static_cast<hipStream_t>(stream)), what);
+    }
+    mglu::StreamParams p = stream_params(d);
+    p.x = o.x; p.w = o.w; p.w2 = o.w2; p.m = o.m; p.out = o.out;
+    p.proj_t = o.proj_t; p.proj_gate = o.proj_gate; p.proj_value = o.proj_value;
+    p.gate_fn = o.gate_fn; p.mask_use = o.mask_use; p.route = o.route;
+    p.describe = describe; p.describe_len = describe_len;
+    return hip_result(mglu::launch_stream(p, elem_of(d), mode, static_cast<hipStream_t>(stream)), what);
+}
+
 mglu_status check_bool_inputs(const void *x_dev, const void *W_dev, const uint8_t *masks_dev, const void *out_dev)
 {
     MGLU_TRY(check_ptr(x_dev, "x_dev"));
@@ -245,28 +276,10 @@ mglu_status mglu_forward_variant(const mglu_desc *desc, const mglu_variant *vari
     }
     // the main form (Swish, both branches masked, no route weights) runs the kernels without the run-time choices
     const int mode = (gate_fn != 0 || mask_use != 0 || route) ? mglu::kModeMgluVariant : mglu::kModeMglu;
-    if (use_tiled_kernel(desc, desc->n_masks)) {
-        mglu::PrefillParams pp = prefill_params(desc);
-        pp.x = x_dev;
-        pp.w = W_packed_dev;
-        pp.m = static_cast<const uint32_t *>(masks_packed_dev);
-        pp.out = out_dev;
-        pp.gate_fn = gate_fn;
-        pp.mask_use = mask_use;
-        pp.route = route;
-        return hip_result(mglu::launch_prefill(pp, elem_of(desc), mode, static_cast<hipStream_t>(stream)),
-                          "mglu_forward (prefill) launch");
-    }
-    mglu::StreamParams p = stream_params(desc);
-    p.x = x_dev;
-    p.w = W_packed_dev;
-    p.m = static_cast<const uint32_t *>(masks_packed_dev);
-    p.out = out_dev;
-    p.gate_fn = gate_fn;
-    p.mask_use = mask_use;
-    p.route = route;
-    return hip_result(mglu::launch_stream(p, elem_of(desc), mode, static_cast<hipStream_t>(stream)),
-                      "mglu_forward launch");
+    Operands o = {};
+    o.x = x_dev; o.w = W_packed_dev; o.m = static_cast<const uint32_t *>(masks_packed_dev); o.out = out_dev;
+    o.gate_fn = gate_fn; o.mask_use = mask_use; o.route = route;
+    return run_layer(desc, mode, o, stream, "mglu_forward launch");
 }
 
 mglu_status mglu_forward(const mglu_desc *desc, const void *x_dev, const void *W_packed_dev,
@@ -313,20 +326,9 @@ mglu_status mglu_linear_forward(const mglu_desc *desc, const void *a_dev, const 
     MGLU_TRY(check_ptr(out_dev, "out_dev"));
     (void)workspace_dev;
     (void)workspace_bytes;
-    if (use_tiled_kernel(desc, 1)) {
-        mglu::PrefillParams pp = prefill_params(desc);
-        pp.x = a_dev;
-        pp.w = W_packed_dev;
-        pp.out = out_dev;
-        return hip_result(mglu::launch_prefill(pp, elem_of(desc), mglu::kModeLinear, static_cast<hipStream_t>(stream)),
-                          "mglu_linear_forward (prefill) launch");
-    }
-    mglu::StreamParams p = stream_params(desc);
-    p.x = a_dev;
-    p.w = W_packed_dev;
-    p.out = out_dev;
-    return hip_result(mglu::launch_stream(p, elem_of(desc), mglu::kModeLinear, static_cast<hipStream_t>(stream)),
-                      "mglu_linear_forward launch");
+    Operands o = {};
+    o.x = a_dev; o.w = W_packed_dev; o.out = out_dev;
+    return run_layer(desc, mglu::kModeLinear, o, stream, "mglu_linear_forward launch");
 }
 
 mglu_status mglu_ffn_forward(const mglu_desc *desc, const mglu_variant *variant, const void *x_dev,
@@ -409,16 +411,10 @@ mglu_status mglu_projections(const mglu_desc *desc, const void *x_dev, const voi
     if (value_dev) MGLU_TRY(check_ptr(value_dev, "value_dev"));
     (void)workspace_dev;
     (void)workspace_bytes;
-    mglu::StreamParams p = stream_params(desc);
-    p.x = x_dev;
-    p.w = W_packed_dev;
-    p.m = static_cast<const uint32_t *>(masks_packed_dev);
-    p.proj_t = t_dev;
-    p.proj_gate = gate_dev;
-    p.proj_value = value_dev;
-    return hip_result(mglu::launch_stream(p, elem_of(desc), mglu::kModeProjections,
-                                          static_cast<hipStream_t>(stream)),
-                      "mglu_projections launch");
+    Operands o = {};
+    o.x = x_dev; o.w = W_packed_dev; o.m = static_cast<const uint32_t *>(masks_packed_dev);
+    o.proj_t = t_dev; o.proj_gate = gate_dev; o.proj_value = value_dev;
+    return run_layer(desc, mglu::kModeProjections, o, stream, "mglu_projections launch");
 }
 
 mglu_status swiglu_forward(const mglu_desc *desc, const void *x_dev, const void *Wg_packed_dev,
@@ -432,22 +428,26 @@ mglu_status swiglu_forward(const mglu_desc *desc, const void *x_dev, const void 
     MGLU_TRY(check_ptr(out_dev, "out_dev"));
     (void)workspace_dev;
     (void)workspace_bytes;
-    if (use_tiled_kernel(desc, 1)) {
-        mglu::PrefillParams pp = prefill_params(desc);
-        pp.x = x_dev;
-        pp.w = Wg_packed_dev;
-        pp.w2 = Wv_packed_dev;
-        pp.out = out_dev;
-        return hip_result(mglu::launch_prefill(pp, elem_of(desc), mglu::kModeSwiglu, static_cast<hipStream_t>(stream)),
-                          "swiglu_forward (prefill) launch");
+    Operands o = {};
+    o.x = x_dev; o.w = Wg_packed_dev; o.w2 = Wv_packed_dev; o.out = out_dev;
+    return run_layer(desc, mglu::kModeSwiglu, o, stream, "swiglu_forward launch");
+}
+
+mglu_status mglu_describe_plan(const mglu_desc *desc, mglu_call call, char *buf, size_t len)
+{
+    if (!buf || len == 0) return fail(MGLU_ERR_INVALID_ARG, "buf is NULL or has no room");
+    buf[0] = '\0';
+    int mode;
+    switch (call) {
+    case MGLU_CALL_FORWARD: mode = mglu::kModeMglu; break;
+    case MGLU_CALL_FORWARD_VARIANT: mode = mglu::kModeMgluVariant; break;
+    case MGLU_CALL_PROJECTIONS: mode = mglu::kModeProjections; break;
+    case MGLU_CALL_LINEAR: mode = mglu::kModeLinear; break;
+    case MGLU_CALL_SWIGLU: mode = mglu::kModeSwiglu; break;
+    default: return fail(MGLU_ERR_INVALID_ARG, "call %d is not a mglu_call", (int)call);
     }
-    mglu::StreamParams p = stream_params(desc);
-    p.x = x_dev;
-    p.w = Wg_packed_dev;
-    p.w2 = Wv_packed_dev;
-    p.out = out_dev;
-    return hip_result(mglu::launch_stream(p, elem_of(desc), mglu::kModeSwiglu, static_cast<hipStream_t>(stream)),
-                      "swiglu_forward launch");
+    MGLU_TRY(check_forward(desc, mode != mglu::kModeLinear && mode != mglu::kModeSwiglu));
+    return run_layer(desc, mode, Operands{}, nullptr, "mglu_describe_plan", buf, len);
 }
 
 mglu_status mglu_stream_read(const void *buf_dev, size_t bytes, uint32_t *sink_dev, void *stream)

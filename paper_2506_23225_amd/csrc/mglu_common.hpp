@@ -251,6 +251,12 @@ struct F32Traits {
     __device__ static __forceinline__ void store1(void *out, long idx, float v) { static_cast<float *>(out)[idx] = v; }
 };
 
+// the traits' names as they appear in a kernel instantiation's name (host side, for the plan query)
+template <typename Tr> constexpr const char *traits_name();
+template <> constexpr const char *traits_name<Bf16Traits>() { return "Bf16Traits"; }
+template <> constexpr const char *traits_name<F16Traits>() { return "F16Traits"; }
+template <> constexpr const char *traits_name<F32Traits>() { return "F32Traits"; }
+
 // ---- what a launch computes ---------------------------------------------------------------
 enum Mode {
     kModeMglu = 0,         // out = sum_i swish(gate_i) * value_i             (Eq. 3)

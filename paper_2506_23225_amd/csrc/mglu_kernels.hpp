@@ -22,6 +22,8 @@ struct StreamParams {
     int gate_fn;          // epilogue variant: see EpilogueParams
     int mask_use;
     const float *route;   // [T][n_masks] route weights, may be null
+    char *describe;       // host only: if set, the launcher writes the kernel instantiation it would launch
+    size_t describe_len;  //            here (as text) and launches nothing
 };
 
 struct PrefillParams {
@@ -37,6 +39,8 @@ struct PrefillParams {
     int gate_fn;          // epilogue variant: see EpilogueParams
     int mask_use;
     const float *route;   // [T][n_masks] route weights, may be null
+    char *describe;       // host only: see StreamParams
+    size_t describe_len;
 };
 
 struct RouteParams {

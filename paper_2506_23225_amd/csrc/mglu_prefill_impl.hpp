@@ -22,6 +22,8 @@
 // Workgroup ids are remapped so that the workgroups resident on one XCD (ids equal mod 8)
 // cover a compact patch of tiles and share W / x through that XCD's L2.
 #pragma once
+#include <stdio.h>
+
 #include <type_traits>
 
 #include "mglu_common.hpp"
@@ -257,9 +259,13 @@ void prefill_kernel(PrefillParams p)
             asm volatile("s_waitcnt lgkmcnt(%1)" : "+v"(b) : "n"(newer));
         };
         frag btile[MASK_MAJOR ? 2 : 1][TB];
-        frag bcur[2], bnxt[2];
+        // Two pairs of B fragments used in turn: step n of a chunk multiplies bp[n & 1] while bp[(n + 1) & 1]
+        // is being read.  The parity is a compile-time constant of the unrolled code, so every read is
+        // waited for in the very registers it writes (no register copy of a read still in flight); a
+        // chunk has an even number of steps, so every chunk starts with bp[0].
+        frag bp[2][2];
         if constexpr (MASK_MAJOR) read_tile(btile[0], 0);
-        else read_pair(bcur, 0, 0);
+        else read_pair(bp[0], 0, 0);
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
             // Issue this tile's prefetches first: pieces of the next chunk's x (stored one tile
@@ -333,8 +339,9 @@ void prefill_kernel(PrefillParams p)
                 // two MFMAs and dropped after them (all variants at once would not fit the registers);
                 // the issue-order groups keep the compiler from gathering the preparation up front.
                 const bool more = t + 1 < 4;
+                frag (&bcur)[2] = bp[t & 1];
                 if (more) {
-                    read_pair(bnxt, t + 1, 0);
+                    read_pair(bp[(t + 1) & 1], t + 1, 0);
                     asm volatile("s_waitcnt lgkmcnt(2)" : "+v"(bcur[0]), "+v"(bcur[1]));
                 } else {
                     asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(bcur[0]), "+v"(bcur[1]));
@@ -353,7 +360,6 @@ void prefill_kernel(PrefillParams p)
                         __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
                     }
                 }
-                if (more) { bcur[0] = bnxt[0]; bcur[1] = bnxt[1]; }
             } else {
                 // operand variants of this tile: W itself and W with mask i's gate elements negated
                 frag var[SETS][CB];
@@ -370,8 +376,10 @@ void prefill_kernel(PrefillParams p)
     #pragma unroll
                 for (int pi = 0; pi < PAIRS; ++pi) {
                     const bool more = (pi + 1 < PAIRS) || (t + 1 < 4);
+                    static_assert(MASK_MAJOR || (4 * PAIRS) % 2 == 0, "a chunk must have an even number of steps");
+                    frag (&bcur)[2] = bp[(t * PAIRS + pi) & 1];
                     if (more) {
-                        read_pair(bnxt, pi + 1 < PAIRS ? t : t + 1, pi + 1 < PAIRS ? pi + 1 : 0);
+                        read_pair(bp[(t * PAIRS + pi + 1) & 1], pi + 1 < PAIRS ? t : t + 1, pi + 1 < PAIRS ? pi + 1 : 0);
                         asm volatile("s_waitcnt lgkmcnt(2)" : "+v"(bcur[0]), "+v"(bcur[1]));
                     } else {
                         asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(bcur[0]), "+v"(bcur[1]));
@@ -383,7 +391,6 @@ void prefill_kernel(PrefillParams p)
     #pragma unroll
                             for (int cb = 0; cb < CB; ++cb)
                                 acc[s][cb][2 * pi + h2] = Tr::mma(var[s][cb], bcur[h2], acc[s][cb][2 * pi + h2]);
-                    if (more) { bcur[0] = bnxt[0]; bcur[1] = bnxt[1]; }
                 }
             }
         }
@@ -464,6 +471,11 @@ static hipError_t launch_prefill_one(PrefillParams p, hipStream_t stream)
     const int per_xcd = (p.tiles_n + 7) / 8;
     const long wgs = (long)8 * per_xcd * p.tiles_m;
     const size_t lds = (size_t)kPrefillXBuf * 4 * TB * kWave * sizeof(f32x4);
+    if (p.describe) {   // name the instantiation instead of launching it
+        snprintf(p.describe, p.describe_len, "prefill_kernel<%s, %d, %d, %d, %d, %d, %d>",
+                 traits_name<Tr>(), NMP, CB, TB, MODE, AD, NW);
+        return hipSuccess;
+    }
     auto kern = prefill_kernel<Tr, NMP, CB, TB, MODE, AD, NW>;
     if (lds > 64 * 1024) {   // beyond the default dynamic LDS limit: allowed once per kernel
         static hipError_t allowed = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),

@@ -27,6 +27,8 @@
 // wavefronts that split K with it, so together they read one contiguous run of the packed
 // weight stream at any moment.
 #pragma once
+#include <stdio.h>
+
 #include <type_traits>
 
 #include "mglu_common.hpp"
@@ -701,9 +703,17 @@ static StreamPlan plan_stream(const StreamParams &p, int elem_kind, int nmp, int
 // once it has been allowed to (asked once per kernel instantiation, not per launch).
 constexpr int kMaxDynamicLds = 160 * 1024;
 
-template <typename K>
-static hipError_t launch_kernel(K kern, const StreamParams &p, const StreamPlan &pl, hipStream_t stream)
+template <typename Tr, int NMP, int TB, int MODE, typename Shape>
+static hipError_t launch_panel_one(const StreamParams &p, const StreamPlan &pl, hipStream_t stream)
 {
+    constexpr int NWC = Shape::NWC, NWK = Shape::NWK, CPW = Shape::CPW;
+    if (p.describe) {   // name the instantiation instead of launching it
+        snprintf(p.describe, p.describe_len, "stream_panel_kernel<%s, %d, %d, %d, %d, %d, %d>", traits_name<Tr>(), NMP,
+                 TB, MODE, NWC, NWK, CPW);
+        return hipSuccess;
+    }
+    auto kern = stream_panel_kernel<Tr, NMP, TB, MODE, NWC, NWK, CPW>;
+    // one flag per instantiation (this function is a template over all of the kernel's parameters)
     static hipError_t allowed = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                                                     hipFuncAttributeMaxDynamicSharedMemorySize, kMaxDynamicLds);
     if (pl.lds > 64 * 1024 && allowed != hipSuccess) return allowed;
@@ -711,11 +721,17 @@ static hipError_t launch_kernel(K kern, const StreamParams &p, const StreamPlan 
     return hipGetLastError();
 }
 
-template <typename K>
-static hipError_t launch_resident(K kern, const StreamParams &p, const StreamPlan &pl, hipStream_t stream)
+template <typename Tr, int NMP, int MODE, int R, bool RX>
+static hipError_t launch_resident(const StreamParams &p, const StreamPlan &pl, hipStream_t stream)
 {
-    hipLaunchKernelGGL(kern, pl.grid, pl.block, pl.lds, stream, p.w, p.m, p.x, p.NC, p.T, p.h, p.d, p.out,
-                       pl.nw_shift, p.n_masks, p.NB, p.w2, p.proj_t, p.proj_gate, p.proj_value, p.gate_fn, p.mask_use, p.route);
+    if (p.describe) {
+        snprintf(p.describe, p.describe_len, "stream_resident_kernel<%s, %d, %d, %d, %s>", traits_name<Tr>(), NMP, MODE, R,
+                 RX ? "true" : "false");
+        return hipSuccess;
+    }
+    hipLaunchKernelGGL((stream_resident_kernel<Tr, NMP, MODE, R, RX>), pl.grid, pl.block, pl.lds, stream, p.w, p.m, p.x,
+                       p.NC, p.T, p.h, p.d, p.out, pl.nw_shift, p.n_masks, p.NB, p.w2, p.proj_t, p.proj_gate, p.proj_value,
+                       p.gate_fn, p.mask_use, p.route);
     return hipGetLastError();
 }
 
@@ -723,12 +739,11 @@ template <typename Tr, int NMP, int MODE, typename Shape>
 static hipError_t launch_panel(const StreamParams &p, const StreamPlan &pl, hipStream_t stream)
 {
     constexpr bool kIsBf16 = Tr::ELEM_BYTES == 2;
-    constexpr int NWC = Shape::NWC, NWK = Shape::NWK, CPW = Shape::CPW;
-    if (pl.tb == 1) return launch_kernel(stream_panel_kernel<Tr, NMP, 1, MODE, NWC, NWK, CPW>, p, pl, stream);
+    if (pl.tb == 1) return launch_panel_one<Tr, NMP, 1, MODE, Shape>(p, pl, stream);
     if constexpr (kIsBf16 && NMP <= 8) {
-        if (pl.tb == 2) return launch_kernel(stream_panel_kernel<Tr, NMP, 2, MODE, NWC, NWK, CPW>, p, pl, stream);
+        if (pl.tb == 2) return launch_panel_one<Tr, NMP, 2, MODE, Shape>(p, pl, stream);
         if constexpr (NMP <= 2) {
-            if (pl.tb == 4) return launch_kernel(stream_panel_kernel<Tr, NMP, 4, MODE, NWC, NWK, CPW>, p, pl, stream);
+            if (pl.tb == 4) return launch_panel_one<Tr, NMP, 4, MODE, Shape>(p, pl, stream);
         }
     }
     return hipErrorInvalidValue;
@@ -740,9 +755,9 @@ static hipError_t launch_plan(const StreamParams &p, const StreamPlan &pl, hipSt
     if (pl.resident) {
         if constexpr (MODE == kModeMglu && Tr::ELEM_BYTES == 2) {
             if ((long)p.NB * p.NC <= 256L * MGLU_RESIDENT_RX_MAX_CHUNKS_PER_CU)
-                return launch_resident(stream_resident_kernel<Tr, NMP, MODE, MGLU_STREAM_RING, true>, p, pl, stream);
+                return launch_resident<Tr, NMP, MODE, MGLU_STREAM_RING, true>(p, pl, stream);
         }
-        return launch_resident(stream_resident_kernel<Tr, NMP, MODE, MGLU_STREAM_RING, false>, p, pl, stream);
+        return launch_resident<Tr, NMP, MODE, MGLU_STREAM_RING, false>(p, pl, stream);
     }
     return pl.wide ? launch_panel<Tr, NMP, MODE, PanelWide>(p, pl, stream)
                    : launch_panel<Tr, NMP, MODE, PanelSplit>(p, pl, stream);

@@ -80,13 +80,32 @@ def test_prefill_kernel_ragged_shapes(T, h, d, n_m):
     ("bf16", 1000, 320, 4000, 4), ("bf16", 1000, 136, 4090, 3), ("f16", 1000, 264, 4000, 4), ("bf16", 250, 256, 16300, 4),
 ])
 def test_prefill_four_masks_tall_tile(dtype, T, h, d, n_m):
-    """With three or four masks the tiled kernel picks a 96- or a 128-token tile per launch (whichever
-    covers the chip in less work).  These launches are large enough for the 128-token tile -- the small
-    ragged shapes above all take the 96-token one -- with ragged token, column and reduction tails."""
+    """With three or four masks the tiled kernel picks one of four tile shapes per launch (whichever covers
+    the chip in the least estimated time).  These launches are large enough for the 8-wavefront 128-token
+    tile, with ragged token, column and reduction tails; the other three shapes have cases of their own
+    below and in tests/test_gpu_plan_parity.py."""
     x, W, masks = synth.make_inputs(h, d, n_m, T, dtype=dtype, seed=T + h + d, device=DEV)
     out = _run(x, W, masks)
     if d > 4096:
         _check_columns(x, W, masks, out, edge_columns(d, n_random=256, seed=T))
+    else:
+        _check_full(x, W, masks, out)
+
+
+@pytest.mark.parametrize("dtype,T,h,d,n_m,tile", [
+    ("bf16", 80, 264, 28672, 4, "1, 6, 0, 2, 8"), ("bf16", 96, 136, 28660, 3, "1, 6, 0, 2, 8"),
+    ("f16", 70, 392, 28672, 4, "1, 6, 0, 2, 8"), ("bf16", 390, 264, 28672, 4, "1, 8, 0, 3, 4"),
+    ("bf16", 400, 136, 28650, 3, "1, 8, 0, 3, 4"), ("bf16", 100, 520, 1000, 4, "1, 4, 0, 6, 4"),
+])
+def test_prefill_four_masks_other_tiles(dtype, T, h, d, n_m, tile):
+    """The four-mask kernel's 96-token mask-major tile, its 4-wavefront 128-token tile and its 4-wavefront
+    64-token tile, each asserted through the plan query, on ragged shapes."""
+    x, W, masks = synth.make_inputs(h, d, n_m, T, dtype=dtype, seed=T + h + d, device=DEV)
+    traits = {"bf16": "Bf16Traits", "f16": "F16Traits"}[dtype]
+    assert api.mglu_describe_plan(api.make_desc(T, h, d, n_m, x.dtype)) == "prefill_kernel<%s, 4, %s>" % (traits, tile)
+    out = _run(x, W, masks)
+    if d > 4096:
+        _check_columns(x, W, masks, out, edge_columns(d, n_random=128, seed=T))
     else:
         _check_full(x, W, masks, out)
 
@@ -199,6 +218,16 @@ def test_decode_8b_config_sampled(T):
     print("decode_8b T=%d rel err" % T, _check_columns(x, W, masks, out, edge_columns(cfg["d_ff"])))
 
 
+def test_decode_8b_sixteen_masks_sampled():
+    """4096 x 14336 with 16 masks at one token: the benchmark's 16-mask decode row."""
+    cfg = synth.config("decode_8b", n_masks=16, tokens=1)
+    x, W, masks = synth.make_inputs(**cfg, seed=0, device=DEV)
+    assert api.mglu_describe_plan(api.make_desc(1, 4096, 14336, 16, x.dtype)) == \
+        "stream_resident_kernel<Bf16Traits, 16, 0, 2, false>"
+    out = _run(x, W, masks)
+    print("decode_8b n_m=16 rel err", _check_columns(x, W, masks, out, edge_columns(cfg["d_ff"])))
+
+
 def test_prefill_8b_config_sampled():
     """Full-size prefill configuration: all 4096 tokens on sampled columns (tile edges, tail, random)."""
     cfg = synth.config("prefill_8b")
@@ -207,8 +236,10 @@ def test_prefill_8b_config_sampled():
     print("prefill_8b rel err", _check_columns(x, W, masks, out, edge_columns(cfg["d_ff"], n_random=48)))
 
 
-@pytest.mark.parametrize("n_m,T", [(1, 1), (2, 32), (4, 1), (8, 32), (1, 2048), (8, 2048)])
+@pytest.mark.parametrize("T", [1, 32, 2048])
+@pytest.mark.parametrize("n_m", [1, 2, 4, 8])
 def test_large_config_sampled(n_m, T):
+    """Every cell of the large layer sweep (8192 x 28672), each in the launch configuration the benchmark times."""
     cfg = synth.config("large", n_masks=n_m, tokens=T)
     x, W, masks = synth.make_inputs(**cfg, seed=0, device=DEV)
     out = _run(x, W, masks)
