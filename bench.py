@@ -106,6 +106,20 @@ class Workload:
         Wp, Mp = self.ring[i % self.copies]
         self.api.mglu_forward_variant(self.desc, self.x, Wp, Mp, route_weights=self.route, out=self.out, workspace=self.ws)
 
+    def enable_planar_routing(self, k, masks):
+        """The same routed layer on the planar mask format: a ring of (W, planar masks) copies; only k planes are read."""
+        from paper_2506_23225_amd import costmodel
+        self.route_k = k
+        Mpl = self.api.mglu_pack_masks_planar(self.desc, masks)
+        self.planar_ring = [(Wp, Mpl if j == 0 else Mpl.clone()) for j, (Wp, _) in enumerate(self.ring)]
+        c = self.cfg
+        self.routed_bytes = costmodel.mglu_bytes(c["d_model"], c["d_ff"], k, c["tokens"], c["dtype"])   # W + k planes
+        self.routed_flops = costmodel.mglu_flops(c["d_model"], c["d_ff"], k, c["tokens"])               # t + k masked sums
+
+    def planar_routed_step(self, i):
+        Wp, Mpl = self.planar_ring[i % self.copies]
+        self.api.mglu_forward_routed(self.desc, self.x, Wp, Mpl, self.route, self.route_k, out=self.out)
+
     def enable_ffn(self, ring_bytes=2 * LLC_BYTES):
         torch = self.torch
         T, h, d = self.cfg["tokens"], self.cfg["d_model"], self.cfg["d_ff"]
@@ -419,12 +433,21 @@ def run_widened(torch, synth, only, timer):
     for name, cfg, kind, steps, warmup in cases:
         if only and not any(o in name for o in only):
             continue
-        w = Workload(name, cfg, swiglu=False)
+        w = Workload(name, cfg, swiglu=False, keep_inputs=(kind == "routed"))
         if kind == "routed":
             w.enable_routing(2)
-            t = timer.run(w.routed_step, steps, warmup)
+            w.enable_planar_routing(2, w.inputs[2])
+            w.inputs = None
+            # interleaved mask format first (every mask's bits stream, the unselected masks' sums are skipped) ...
+            ti = timer.run(w.routed_step, steps, warmup)
+            # ... then the planar format: only the two selected planes are read; bytes credited = W + 2 planes
+            t = timer.run(w.planar_routed_step, steps, warmup)
+            w.bytes, w.flops = w.routed_bytes, w.routed_flops
             rec = summarize(w, t, "hbm")
-            rec["kernel"] = w.api.mglu_describe_plan(w.desc, "forward_variant")
+            rec["kernel"] = w.api.mglu_describe_plan(w.desc, "forward_routed", 2)
+            rec["interleaved_format_ms"] = ti["ms"]
+            rec["interleaved_format_kernel"] = w.api.mglu_describe_plan(w.desc, "forward_variant")
+            rec["note"] = "planar mask format: bytes credited are W + the 2 selected mask planes"
         else:
             w.enable_ffn()
             t = timer.run(w.ffn_step, steps, warmup)

@@ -179,7 +179,8 @@ typedef struct {
      * With at most 16 tokens (x resident in LDS) a mask whose weight is 0 for every token of the
      * call gets no sum at all -- no operand preparation, no MFMA; the selected masks share the
      * accumulators in compact order.  With more tokens every term is computed and then weighted.
-     * The masks' bits stream from memory whatever the selection, so the saving is arithmetic only. */
+     * The masks' bits stream from memory whatever the selection, so the saving is arithmetic only
+     * (mglu_forward_routed with the planar mask format skips the bytes too). */
     const float *route_weights_dev;
 } mglu_variant;
 
@@ -194,6 +195,34 @@ mglu_status mglu_forward_variant(const mglu_desc *desc, const mglu_variant *vari
  *   weights_dev fp32 [tokens][n_masks], fully overwritten.  desc->d_ff is ignored. */
 mglu_status mglu_route_topk(const mglu_desc *desc, const void *x_dev, const void *Wr_dev, int k,
                             float *weights_dev, void *stream);
+
+/* ---- Top-K routed layer that reads only the selected masks (appendix "Top-K Routing") ------- */
+
+/* The appendix notes that with Top-K routing only the K selected masked projections need be
+ * evaluated, which cuts memory traffic as well as arithmetic.  The interleaved format of
+ * mglu_pack_masks keeps the bits of all masks of an element side by side, so every mask's bits
+ * stream whatever the selection.  This second, PLANAR format stores each mask's bit plane on its
+ * own -- per column block and mask one contiguous run of 32-bit words, word = the 32 bits of that
+ * mask for the 32 weight elements one lane holds in a chunk -- and mglu_forward_routed loads the
+ * planes of the selected masks only: top-2 of 8 masks moves 16 + 2 instead of 16 + 8 bits per
+ * weight element.  Exactly n_masks planes are stored (no rounding up). */
+size_t mglu_packed_mask_bytes_planar(const mglu_desc *desc);
+mglu_status mglu_pack_masks_planar(const mglu_desc *desc, const uint8_t *masks_dev, void *packed_dev, void *stream);
+
+/* out = sum_i G(x)_i g(x (M_i*W)) * x ((1-M_i)*W) over the masks with a non-zero weight.
+ *   masks_planar_dev   from mglu_pack_masks_planar
+ *   route_weights_dev  fp32 [tokens][n_masks], e.g. from mglu_route_topk
+ *   k                  how many weights per token may be non-zero (1 <= k <= n_masks): sizes the
+ *                      kernel (accumulators for min(n_masks, k * tokens) masks, rounded up to 2, 4, 8
+ *                      or 16).  The result is right for ANY weights: if more distinct masks turn out
+ *                      to be selected than that, the kernel makes further passes over W for them.
+ *   gate               the gate function g (MGLU_GATE_SWISH for the paper's routed SwiMGLU)
+ * For at most 16 tokens whose rows of x fit the kernel's LDS budget (every decode shape of up to
+ * ~28 K d_model at one token, 4096 at four); otherwise MGLU_ERR_UNSUPPORTED -- pack with
+ * mglu_pack_masks and use mglu_forward_variant, which weights every mask's term, instead. */
+mglu_status mglu_forward_routed(const mglu_desc *desc, const void *x_dev, const void *W_packed_dev,
+                                const void *masks_planar_dev, const float *route_weights_dev, int k,
+                                mglu_gate_fn gate, void *out_dev, void *stream);
 
 /* Plain projection out = a W with the same packed weight format and kernels (no masks, no
  * activation): the output projection W_o in R^{d x h} that maps the layer's result back to the
@@ -234,16 +263,18 @@ typedef enum {
     MGLU_CALL_FORWARD_VARIANT = 1,  /* mglu_forward_variant with any variation switched on */
     MGLU_CALL_PROJECTIONS = 2,      /* mglu_projections */
     MGLU_CALL_LINEAR = 3,           /* mglu_linear_forward */
-    MGLU_CALL_SWIGLU = 4            /* swiglu_forward */
+    MGLU_CALL_SWIGLU = 4,           /* swiglu_forward */
+    MGLU_CALL_FORWARD_ROUTED = 5    /* mglu_forward_routed */
 } mglu_call;
 
 /* Writes into buf (len bytes, always NUL-terminated) the name of the kernel instantiation that
  * `call` would launch for this descriptor -- kernel family and template arguments as in the
  * library's symbol table, e.g. "stream_resident_kernel<Bf16Traits, 8, 0, 2, false>" -- without
  * launching anything or touching a GPU.  The same checks as the call itself apply to the
- * descriptor.  Lets a test suite assert which code path a shape exercises, and that every
- * instantiation the library can select is covered by a parity test. */
-mglu_status mglu_describe_plan(const mglu_desc *desc, mglu_call call, char *buf, size_t len);
+ * descriptor; route_k is the `k` of mglu_forward_routed and ignored for every other call.  Lets a
+ * test suite assert which code path a shape exercises, and that every instantiation the library
+ * can select is covered by a parity test. */
+mglu_status mglu_describe_plan(const mglu_desc *desc, mglu_call call, int route_k, char *buf, size_t len);
 
 /* ---- errors -------------------------------------------------------------------------------- */
 const char *mglu_last_error(void);              /* thread-local, never NULL */

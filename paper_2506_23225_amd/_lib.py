@@ -22,7 +22,7 @@ class MgluVariant(ctypes.Structure):
     _fields_ = [("gate", ctypes.c_int), ("mask_use", ctypes.c_int), ("route_weights_dev", ctypes.c_void_p)]
 
 
-MGLU_CALL = {"forward": 0, "forward_variant": 1, "projections": 2, "linear": 3, "swiglu": 4}
+MGLU_CALL = {"forward": 0, "forward_variant": 1, "projections": 2, "linear": 3, "swiglu": 4, "forward_routed": 5}
 MGLU_GATE = {"swish": 0, "gelu": 1, "relu": 2}
 MGLU_MASK_USE = {"both": 0, "dense_gate": 1, "dense_value": 2, "none": 3}
 
@@ -48,7 +48,10 @@ SIGNATURES = {
     "mglu_ffn_forward": (ctypes.c_int, [_D, ctypes.POINTER(MgluVariant), _P, _P, _P, _P, _P, _P, _P, _SZ, _P]),
     "swiglu_forward": (ctypes.c_int, [_D, _P, _P, _P, _P, _P, _SZ, _P]),
     "mglu_stream_read": (ctypes.c_int, [_P, _SZ, _P, _P]),
-    "mglu_describe_plan": (ctypes.c_int, [_D, ctypes.c_int, ctypes.c_char_p, _SZ]),
+    "mglu_describe_plan": (ctypes.c_int, [_D, ctypes.c_int, ctypes.c_int, ctypes.c_char_p, _SZ]),
+    "mglu_packed_mask_bytes_planar": (_SZ, [_D]),
+    "mglu_pack_masks_planar": (ctypes.c_int, [_D, _P, _P, _P]),
+    "mglu_forward_routed": (ctypes.c_int, [_D, _P, _P, _P, _P, ctypes.c_int, ctypes.c_int, _P, _P]),
     "mglu_last_error": (ctypes.c_char_p, []),
     "mglu_status_string": (ctypes.c_char_p, [ctypes.c_int]),
 }

@@ -156,6 +156,35 @@ def mglu_forward_variant(desc, x, W_packed, masks_packed, gate="swish", mask_use
     return out
 
 
+def mglu_packed_mask_bytes_planar(desc):
+    return _lib.load().mglu_packed_mask_bytes_planar(desc)
+
+
+def mglu_pack_masks_planar(desc, masks, packed=None):
+    """masks uint8/bool as for mglu_pack_masks -> the planar packed buffer that mglu_forward_routed reads."""
+    if masks.dtype == torch.bool:
+        masks = masks.view(torch.uint8)
+    _expect_layer(desc, masks=masks)
+    if packed is None:
+        packed = torch.empty(mglu_packed_mask_bytes_planar(desc), dtype=torch.uint8, device=masks.device)
+    _expect(packed, "packed", min_bytes=mglu_packed_mask_bytes_planar(desc))
+    _check(_lib.load().mglu_pack_masks_planar(desc, _ptr(masks, "masks"), _ptr(packed, "packed"), _stream(masks)))
+    return packed
+
+
+def mglu_forward_routed(desc, x, W_packed, masks_planar, route_weights, k, gate="swish", out=None):
+    """The Top-K routed layer on the planar mask format: only the selected masks' planes are read."""
+    if out is None:
+        out = torch.empty(desc.tokens, desc.d_ff, dtype=x.dtype, device=x.device)
+    _expect_layer(desc, x=x, out=out, W_packed=W_packed)
+    _expect(masks_planar, "masks_planar", min_bytes=mglu_packed_mask_bytes_planar(desc))
+    _expect(route_weights, "route_weights", desc.tokens * desc.n_masks, torch.float32)
+    _check(_lib.load().mglu_forward_routed(desc, _ptr(x, "x"), _ptr(W_packed, "W_packed"),
+                                           _ptr(masks_planar, "masks_planar"), _ptr(route_weights, "route_weights"),
+                                           int(k), _lib.MGLU_GATE[gate], _ptr(out, "out"), _stream(x)))
+    return out
+
+
 def mglu_route_topk(desc, x, Wr, k, weights=None):
     """Top-K router: softmax over the k largest logits of x Wr per token, 0 elsewhere; fp32 [T, n_masks]."""
     if weights is None:
@@ -251,10 +280,11 @@ def swiglu_forward(desc, x, Wg_packed, Wv_packed, out=None, workspace=None):
     return out
 
 
-def mglu_describe_plan(desc, call="forward"):
-    """Name of the kernel instantiation `call` would launch for this descriptor (host only, no GPU needed)."""
+def mglu_describe_plan(desc, call="forward", route_k=1):
+    """Name of the kernel instantiation `call` would launch for this descriptor (host only, no GPU needed);
+    route_k is the k of mglu_forward_routed and ignored by the other calls."""
     buf = ctypes.create_string_buffer(256)
-    _check(_lib.load().mglu_describe_plan(desc, _lib.MGLU_CALL[call], buf, len(buf)))
+    _check(_lib.load().mglu_describe_plan(desc, _lib.MGLU_CALL[call], int(route_k), buf, len(buf)))
     return buf.value.decode()
 
 

@@ -14,7 +14,7 @@ OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libmglu.so")
 # the heavy files first: the kernels are instantiated per element type in files of their own so that they compile side by side
 SOURCES = ["mglu_stream_bf16.hip", "mglu_stream_f16.hip", "mglu_stream_f32.hip", "mglu_prefill_bf16.hip",
-           "mglu_prefill_f16.hip", "mglu_api.hip", "mglu_pack.hip", "mglu_stream.hip", "mglu_prefill.hip", "mglu_route.hip"]
+           "mglu_prefill_f16.hip", "mglu_routed.hip", "mglu_api.hip", "mglu_pack.hip", "mglu_stream.hip", "mglu_prefill.hip", "mglu_route.hip"]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wextra",
     "-Wno-unused-command-line-argument",

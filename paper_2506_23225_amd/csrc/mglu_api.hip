@@ -168,6 +168,26 @@ mglu_status run_layer(const mglu_desc *d, int mode, const Operands &o, void *str
     return hip_result(mglu::launch_stream(p, elem_of(d), mode, static_cast<hipStream_t>(stream)), what);
 }
 
+// Shape part of a routed call, checked: k, the gate, and whether the routed kernel covers the shape.
+mglu_status routed_params(const mglu_desc *d, int k, int gate, mglu::RoutedParams *rp)
+{
+    if (k < 1 || k > d->n_masks) return fail(MGLU_ERR_INVALID_ARG, "k=%d must be in [1, n_masks=%d]", k, d->n_masks);
+    if (gate < MGLU_GATE_SWISH || gate > MGLU_GATE_RELU) return fail(MGLU_ERR_INVALID_ARG, "gate %d is not a mglu_gate_fn", gate);
+    rp->T = d->tokens;
+    rp->h = d->d_model;
+    rp->d = d->d_ff;
+    rp->n_masks = d->n_masks;
+    rp->NB = (int)mglu::ceil_div(d->d_ff, mglu::kColBlock);
+    rp->NC = (int)mglu::ceil_div(d->d_model, mglu::kChunkK);
+    rp->gate_fn = gate;
+    rp->k = k;
+    if (!mglu::routed_supported(*rp, elem_of(d)))
+        return fail(MGLU_ERR_UNSUPPORTED,
+                    "mglu_forward_routed covers at most 16 tokens whose rows of x fit its LDS budget (tokens=%d, d_model=%d): "
+                    "pack with mglu_pack_masks and use mglu_forward_variant instead", d->tokens, d->d_model);
+    return MGLU_OK;
+}
+
 mglu_status check_bool_inputs(const void *x_dev, const void *W_dev, const uint8_t *masks_dev, const void *out_dev)
 {
     MGLU_TRY(check_ptr(x_dev, "x_dev"));
@@ -208,7 +228,7 @@ mglu_status static_scratch(char **out)
 
 extern "C" {
 
-int mglu_format_version(void) { return 3; }
+int mglu_format_version(void) { return 4; }
 
 size_t mglu_packed_weight_bytes(const mglu_desc *desc)
 {
@@ -242,6 +262,23 @@ mglu_status mglu_pack_masks(const mglu_desc *desc, const uint8_t *masks_dev, voi
     return hip_result(mglu::launch_pack_masks(pack_params(desc, masks_dev, packed_dev), elem_of(desc),
                                               static_cast<hipStream_t>(stream)),
                       "mglu_pack_masks launch");
+}
+
+size_t mglu_packed_mask_bytes_planar(const mglu_desc *desc)
+{
+    if (check_shape(desc, true) != MGLU_OK) return 0;
+    const size_t nb = mglu::ceil_div(desc->d_ff, mglu::kColBlock), nc = mglu::ceil_div(desc->d_model, mglu::kChunkK);
+    return nb * nc * mglu::kWave * (size_t)desc->n_masks * sizeof(uint32_t);
+}
+
+mglu_status mglu_pack_masks_planar(const mglu_desc *desc, const uint8_t *masks_dev, void *packed_dev, void *stream)
+{
+    MGLU_TRY(check_shape(desc, true));
+    MGLU_TRY(check_ptr(masks_dev, "masks_dev"));
+    MGLU_TRY(check_ptr(packed_dev, "packed_dev"));
+    return hip_result(mglu::launch_pack_masks_planar(pack_params(desc, masks_dev, packed_dev), elem_of(desc),
+                                                     static_cast<hipStream_t>(stream)),
+                      "mglu_pack_masks_planar launch");
 }
 
 size_t mglu_workspace_bytes(const mglu_desc *desc)
@@ -288,6 +325,28 @@ mglu_status mglu_forward(const mglu_desc *desc, const void *x_dev, const void *W
 {
     return mglu_forward_variant(desc, nullptr, x_dev, W_packed_dev, masks_packed_dev, out_dev, workspace_dev,
                                 workspace_bytes, stream);
+}
+
+mglu_status mglu_forward_routed(const mglu_desc *desc, const void *x_dev, const void *W_packed_dev,
+                                const void *masks_planar_dev, const float *route_weights_dev, int k,
+                                mglu_gate_fn gate, void *out_dev, void *stream)
+{
+    MGLU_TRY(check_forward(desc, true));
+    MGLU_TRY(check_ptr(x_dev, "x_dev"));
+    MGLU_TRY(check_ptr(W_packed_dev, "W_packed_dev"));
+    MGLU_TRY(check_ptr(masks_planar_dev, "masks_planar_dev"));
+    MGLU_TRY(check_ptr(out_dev, "out_dev"));
+    if (!route_weights_dev || (reinterpret_cast<uintptr_t>(route_weights_dev) & 3u))
+        return fail(MGLU_ERR_INVALID_ARG, "route_weights_dev is NULL or not 4-byte aligned");
+    mglu::RoutedParams rp = {};
+    MGLU_TRY(routed_params(desc, k, (int)gate, &rp));
+    rp.x = x_dev;
+    rp.w = W_packed_dev;
+    rp.m = static_cast<const uint32_t *>(masks_planar_dev);
+    rp.route = route_weights_dev;
+    rp.out = out_dev;
+    return hip_result(mglu::launch_routed(rp, elem_of(desc), static_cast<hipStream_t>(stream)),
+                      "mglu_forward_routed launch");
 }
 
 mglu_status mglu_route_topk(const mglu_desc *desc, const void *x_dev, const void *Wr_dev, int k,
@@ -433,10 +492,18 @@ mglu_status swiglu_forward(const mglu_desc *desc, const void *x_dev, const void 
     return run_layer(desc, mglu::kModeSwiglu, o, stream, "swiglu_forward launch");
 }
 
-mglu_status mglu_describe_plan(const mglu_desc *desc, mglu_call call, char *buf, size_t len)
+mglu_status mglu_describe_plan(const mglu_desc *desc, mglu_call call, int route_k, char *buf, size_t len)
 {
     if (!buf || len == 0) return fail(MGLU_ERR_INVALID_ARG, "buf is NULL or has no room");
     buf[0] = '\0';
+    if (call == MGLU_CALL_FORWARD_ROUTED) {
+        MGLU_TRY(check_forward(desc, true));
+        mglu::RoutedParams rp = {};
+        MGLU_TRY(routed_params(desc, route_k, MGLU_GATE_SWISH, &rp));
+        rp.describe = buf;
+        rp.describe_len = len;
+        return hip_result(mglu::launch_routed(rp, elem_of(desc), nullptr), "mglu_describe_plan");
+    }
     int mode;
     switch (call) {
     case MGLU_CALL_FORWARD: mode = mglu::kModeMglu; break;

@@ -27,6 +27,12 @@
 // assigned so that registers p and p + 2 (16 masks: p and p + 1) of a fragment find their bits in
 // two neighbouring words at the same position: one 64-bit shift then serves both.
 // fp32: element E = 4t + e, linear = E*NMP + i -> word linear/32, bit linear%32.
+//
+//   planar masks  [jb][mask i < n_masks][kc][lane<64]  uint32
+//
+// the second mask format, for the routed kernel that reads only the selected masks: a word holds the
+// 32 bits of one mask for the 32 elements of its lane (bit = Traits::planar_bit(t, e)), and the words
+// of one mask of one column block are one contiguous run over the chunks.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -166,6 +172,22 @@ struct Half16Common {
     {
         return flip<NMP>(w, m, t, i);
     }
+
+    // Planar mask format: one word holds the 32 bits of ONE mask for the 32 elements a lane holds in a
+    // chunk; element e of tile t (pair e/2, half e%2) has its bit here.
+    __host__ __device__ static constexpr int planar_bit(int t, int e) { return 4 * t + e / 2 + 16 * (e & 1); }
+    // W fragment of tile t flipped by two masks at once (ma, mb: their plane words): the two words ride
+    // in one 64-bit register pair, so one 64-bit shift per register of the fragment serves both masks.
+    __device__ static __forceinline__ void flip_planar2(frag w, uint32_t ma, uint32_t mb, int t, frag &ra, frag &rb)
+    {
+        const uint64_t mm = ((uint64_t)mb << 32) | ma;
+#pragma unroll
+        for (int p = 0; p < 4; ++p) {
+            const uint64_t s = shl64(mm, 15 - (4 * t + p));
+            ra[p] = w[p] ^ ((uint32_t)s & 0x80008000u);
+            rb[p] = w[p] ^ ((uint32_t)(s >> 32) & 0x80008000u);
+        }
+    }
 };
 
 struct Bf16Traits : Half16Common {
@@ -242,6 +264,19 @@ struct F32Traits {
             r[e] = __uint_as_float(__float_as_uint(w[e]) ^ ((m[lin0 >> 5] << (31 - (lin0 & 31) - i)) & 0x80000000u));
         }
         return r;
+    }
+
+    // planar mask format (see Half16Common): element e of tile t is bit 4t + e of a mask's word
+    __host__ __device__ static constexpr int planar_bit(int t, int e) { return 4 * t + e; }
+    __device__ static __forceinline__ void flip_planar2(frag w, uint32_t ma, uint32_t mb, int t, frag &ra, frag &rb)
+    {
+        const uint64_t mm = ((uint64_t)mb << 32) | ma;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const uint64_t s = shl64(mm, 31 - (4 * t + e));
+            ra[e] = __uint_as_float(__float_as_uint(w[e]) ^ ((uint32_t)s & 0x80000000u));
+            rb[e] = __uint_as_float(__float_as_uint(w[e]) ^ ((uint32_t)(s >> 32) & 0x80000000u));
+        }
     }
 
     __device__ static __forceinline__ void store4(void *out, long idx, f32x4 v)

@@ -43,6 +43,21 @@ struct PrefillParams {
     size_t describe_len;
 };
 
+// Routed layer on the planar mask format (mglu_routed.hip)
+struct RoutedParams {
+    const void *x;        // [T][h]
+    const void *w;        // packed weights
+    const uint32_t *m;    // planar packed masks
+    void *out;            // [T][d]
+    const float *route;   // [T][n_masks] route weights
+    int T, h, d, n_masks;
+    int NB, NC;
+    int gate_fn;
+    int k;                // non-zero weights per token the caller promises at most (sizes the kernel)
+    char *describe;       // host only: see StreamParams
+    size_t describe_len;
+};
+
 struct RouteParams {
     const void *x;        // [T][h]
     const void *wr;       // [h][n_masks], same element type as x
@@ -71,7 +86,12 @@ hipError_t launch_prefill(const PrefillParams &p, int elem, int mode, hipStream_
 
 hipError_t launch_route_topk(const RouteParams &p, int elem, hipStream_t stream);
 
+// false if the shape is outside what the routed kernel covers (more than 16 tokens, or rows of x beyond its LDS budget)
+bool routed_supported(const RoutedParams &p, int elem);
+hipError_t launch_routed(const RoutedParams &p, int elem, hipStream_t stream);
+
 hipError_t launch_pack_weights(const PackParams &p, int elem, hipStream_t stream);
 hipError_t launch_pack_masks(const PackParams &p, int elem, hipStream_t stream);
+hipError_t launch_pack_masks_planar(const PackParams &p, int elem, hipStream_t stream);
 
 }  // namespace mglu

@@ -95,6 +95,48 @@ __global__ __launch_bounds__(256) void pack_masks_kernel(PackParams p)
     }
 }
 
+// Planar format: one thread builds, for one lane of one chunk, the word of every mask: bit
+// Tr::planar_bit(t, e) of mask i's word = M_i at the lane's element (t, e).  The words of one mask of
+// one column block are contiguous over the chunks: [jb][i][kc][lane].
+template <typename Tr>
+__global__ __launch_bounds__(256) void pack_masks_planar_kernel(PackParams p)
+{
+    const long total = (long)p.NB * p.NC * kWave;
+    const long gid = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (gid >= total) return;
+    const int lane = (int)(gid % kWave);
+    const long rest = gid / kWave;
+    const int kc = (int)(rest % p.NC);
+    const int jb = (int)(rest / p.NC);
+    const int j = jb * kColBlock + (lane & 15);
+    const uint8_t *src = static_cast<const uint8_t *>(p.src);
+    const long plane = (long)p.h * p.d;
+    uint32_t *dst = static_cast<uint32_t *>(p.dst);
+    for (int i = 0; i < p.n_masks; ++i) {
+        uint32_t word = 0u;
+#pragma unroll
+        for (int t = 0; t < Tr::TILES; ++t) {
+#pragma unroll
+            for (int e = 0; e < Tr::LANE_K; ++e) {
+                const int k = kc * kChunkK + t * Tr::TILE_K + (lane >> 4) * Tr::LANE_K + e;
+                if (j >= p.d || k >= p.h) continue;
+                const long off = p.nk ? (long)j * p.h + k : (long)k * p.d + j;
+                word |= (src[i * plane + off] != 0 ? 1u : 0u) << Tr::planar_bit(t, e);
+            }
+        }
+        dst[(((long)jb * p.n_masks + i) * p.NC + kc) * kWave + lane] = word;
+    }
+}
+
+hipError_t launch_pack_masks_planar(const PackParams &p, int elem, hipStream_t stream)
+{
+    const long total = (long)p.NB * p.NC * kWave;
+    const dim3 grid((unsigned)ceil_div(total, 256)), block(256);
+    if (elem == kElemF32) hipLaunchKernelGGL((pack_masks_planar_kernel<F32Traits>), grid, block, 0, stream, p);
+    else hipLaunchKernelGGL((pack_masks_planar_kernel<Bf16Traits>), grid, block, 0, stream, p);
+    return hipGetLastError();
+}
+
 hipError_t launch_pack_weights(const PackParams &p, int elem, hipStream_t stream)
 {
     const bool is_f32 = elem == kElemF32;   // bf16 and fp16 are both moved as 16-bit words

@@ -12,7 +12,8 @@ import torch
 from paper_2506_23225_amd import api
 
 DTYPES = {"bf16": torch.bfloat16, "f16": torch.float16, "f32": torch.float32}
-CALLS = ("forward", "forward_variant", "projections", "linear", "swiglu")
+CALLS = ("forward", "forward_variant", "projections", "linear", "swiglu", "forward_routed")
+ROUTE_K = (1, 2, 4, 16)    # sizes the routed kernel for 2, 4, 8 or 16 selected masks (with the token count)
 MASK_COUNTS = (1, 2, 4, 8, 16)
 # token counts on both sides of every hand-over: the resident kernel's 16, the panel kernel's token
 # blocks (17-64), the tiled kernel's 64-, 96- and 128-token tiles in one, two and many rows
@@ -24,7 +25,7 @@ SHAPES = ((264, 100), (1024, 25616), (136, 28672), (256, 14400), (8192, 64), (38
 
 
 def enumerate_plans():
-    """{plan name: (cost, dtype name, call, n_masks, tokens, d_model, d_ff)} -- cheapest case per plan."""
+    """{plan name: (cost, dtype name, call, n_masks, tokens, d_model, d_ff, route_k)} -- cheapest case per plan."""
     best = {}
     for dname, call, n_m, T, (h, d) in itertools.product(DTYPES, CALLS, MASK_COUNTS, TOKENS, SHAPES):
         if call in ("linear", "swiglu") and n_m != 1:
@@ -32,8 +33,16 @@ def enumerate_plans():
         if call == "projections" and T > 64:
             continue   # a debug view of the decode kernels' sums; its outputs are (1 + 2 n_m) fp32 planes
         desc = api.make_desc(T, h, d, n_m, DTYPES[dname])
-        plan = api.mglu_describe_plan(desc, call)
         cost = T * h * d * (1 + n_m)
-        if plan not in best or cost < best[plan][0]:
-            best[plan] = (cost, dname, call, n_m, T, h, d)
+        for k in (ROUTE_K if call == "forward_routed" else (0,)):
+            if k > n_m:
+                continue
+            try:
+                plan = api.mglu_describe_plan(desc, call, k)
+            except api.MgluError as e:
+                if call == "forward_routed" and e.status == 2:
+                    continue   # more than 16 tokens, or x beyond the routed kernel's LDS budget
+                raise
+            if plan not in best or cost < best[plan][0]:
+                best[plan] = (cost, dname, call, n_m, T, h, d, k)
     return best

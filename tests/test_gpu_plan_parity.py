@@ -23,12 +23,12 @@ VARIATIONS = (dict(gate="gelu"), dict(gate="relu", mask_use="dense_gate"), dict(
               dict(mask_use="dense_value"))
 
 
-def _route_weights(T, n_m, seed):
-    """Top-2-style weights: two non-zero entries per token summing to 1 (all of them when n_m < 2)."""
+def _route_weights(T, n_m, seed, k=2):
+    """Top-k-style weights: k non-zero entries per token summing to 1 (all of them when n_m < k)."""
     rng = np.random.default_rng(seed)
     w = np.zeros((T, n_m), dtype=np.float32)
     for t in range(T):
-        keep = rng.choice(n_m, size=min(2, n_m), replace=False)
+        keep = rng.choice(n_m, size=min(k, n_m), replace=False)
         v = rng.random(len(keep)).astype(np.float32) + 0.25
         w[t, keep] = v / v.sum()
     return w
@@ -36,11 +36,11 @@ def _route_weights(T, n_m, seed):
 
 @pytest.mark.parametrize("index", range(len(PLANS)), ids=[name for name, _ in PLANS])
 def test_every_selectable_instantiation(index):
-    plan, (_, dname, call, n_m, T, h, d) = PLANS[index]
-    print("plan case:", plan, dname, call, "n_m=%d T=%d h=%d d=%d" % (n_m, T, h, d), flush=True)
+    plan, (_, dname, call, n_m, T, h, d, k) = PLANS[index]
+    print("plan case:", plan, dname, call, "n_m=%d T=%d h=%d d=%d k=%d" % (n_m, T, h, d, k), flush=True)
     x, W, masks = synth.make_inputs(h, d, n_m, T, dtype=dname, seed=index, device=DEV)
     desc = api.make_desc(T, h, d, n_m, x.dtype)
-    assert api.mglu_describe_plan(desc, call) == plan
+    assert api.mglu_describe_plan(desc, call, k) == plan
     cols = np.arange(d) if d <= 512 else edge_columns(d, n_random=48, seed=index)
     ci = torch.as_tensor(cols, device=DEV)
     xs, Ws, Ms = to_np64(x), to_np64(W[:, ci]), masks[:, :, ci].cpu().numpy()
@@ -54,6 +54,12 @@ def test_every_selectable_instantiation(index):
         _, Wv, _ = synth.make_inputs(h, d, 1, 1, dtype=dname, seed=index + 1000, device=DEV)
         out = api.swiglu_forward(desc, x, Wp, api.mglu_pack_weights(desc, Wv))
         assert rel_err(to_np64(out[:, ci]), oracle.swiglu_forward(xs, Ws, to_np64(Wv[:, ci]))) <= tol
+        return
+    if call == "forward_routed":
+        route = _route_weights(T, n_m, index, k)
+        out = api.mglu_forward_routed(desc, x, Wp, api.mglu_pack_masks_planar(desc, masks),
+                                      torch.as_tensor(route, device=DEV), k)
+        assert rel_err(to_np64(out[:, ci]), oracle.mglu_forward_variant(xs, Ws, Ms, route=route)) <= tol
         return
     Mp = api.mglu_pack_masks(desc, masks)
     if call == "forward":

@@ -26,7 +26,7 @@ def _compiled_kernels():
     out = subprocess.run([nm, "-C", _lib.LIB_PATH], capture_output=True, text=True, check=True).stdout
     names = set()
     for line in out.splitlines():
-        m = re.search(r"__device_stub__((?:stream_resident|stream_panel|prefill)_kernel<.*>)\(", line)
+        m = re.search(r"__device_stub__((?:stream_resident|stream_panel|stream_routed|prefill)_kernel<.*>)\(", line)
         if m:
             names.add(m.group(1).replace("mglu::", ""))
     return names
@@ -60,9 +60,12 @@ def test_describe_plan_rejects_bad_arguments(lib):
     import ctypes
     ok = _lib.MgluDesc(1, 256, 64, 2, _lib.MGLU_BF16, _lib.MGLU_W_KN)
     buf = ctypes.create_string_buffer(8)
-    assert lib.mglu_describe_plan(ok, 0, buf, 8) == 0 and buf.value == b"stream_"   # truncated, NUL-terminated
-    assert lib.mglu_describe_plan(ok, 9, buf, 8) == 1
-    assert lib.mglu_describe_plan(ok, 0, None, 8) == 1
-    assert lib.mglu_describe_plan(None, 0, buf, 8) == 1
+    assert lib.mglu_describe_plan(ok, 0, 0, buf, 8) == 0 and buf.value == b"stream_"   # truncated, NUL-terminated
+    assert lib.mglu_describe_plan(ok, 9, 0, buf, 8) == 1
+    assert lib.mglu_describe_plan(ok, 0, 0, None, 8) == 1
+    assert lib.mglu_describe_plan(None, 0, 0, buf, 8) == 1
     bad = _lib.MgluDesc(1, 100, 64, 2, _lib.MGLU_BF16, _lib.MGLU_W_KN)
-    assert lib.mglu_describe_plan(bad, 0, buf, 8) == 2
+    assert lib.mglu_describe_plan(bad, 0, 0, buf, 8) == 2
+    assert lib.mglu_describe_plan(ok, 5, 3, buf, 8) == 1          # routed: k beyond n_masks
+    many = _lib.MgluDesc(17, 256, 64, 2, _lib.MGLU_BF16, _lib.MGLU_W_KN)
+    assert lib.mglu_describe_plan(many, 5, 1, buf, 8) == 2        # routed: more than 16 tokens
