@@ -10,7 +10,7 @@ rate is an HBM rate, not a cache rate.  One JSON line is printed; the other conf
 ride along under "extra", each with the step counts it was timed with.
 
 Timing method (every row): W warm-up steps, then an untimed settle phase (more of the same
-steps until the GPU has been busy for ~30 ms, so that the shader clock has settled), then a
+steps until the GPU has been busy for ~100 ms, so that the shader clock has settled), then a
 blocker (a few launches of the library's plain read kernel) behind which the K timed steps
 are queued, so that they run back to back on the device whatever the host's launch rate;
 HIP events on the launch stream bracket exactly the K steps, with a synchronisation on both
@@ -33,7 +33,7 @@ LLC_BYTES = 256 * 2 ** 20    # last-level (Infinity) cache
 HEADLINE = "large 8192x28672 n_m=8 T=1"
 HEADLINE_KERNEL = "mglu::stream_resident_kernel<mglu::Bf16Traits, 8, 0, 2, false>"
 HEADLINE_TRAFFIC_KEY = "large_nm8_T1"
-SETTLE_MS = 30.0
+SETTLE_MS = 100.0
 
 
 def parse_args():
@@ -46,8 +46,8 @@ def parse_args():
     ap.add_argument("--no-refs", action="store_true",
                     help="skip the SwiGLU-reference and read-ceiling legs of the headline")
     ap.add_argument("--probe", default="",
-                    help="profiling aid: launch only this workload ('headline' or a substring of an extra "
-                         "workload's name) 20 times, then one mglu_stream_read and one device copy of "
+                    help="profiling aid: launch only this workload ('headline', a substring of an extra "
+                         "workload's name, or 'routed decode_8b' / 'routed large') 20 times, then one mglu_stream_read and one device copy of "
                          "exactly 1 GiB each (known sizes to scale byte counters by), print nothing")
     ap.add_argument("--only", default="", help="comma list of extra workloads to run (names as printed)")
     return ap.parse_args()
@@ -182,7 +182,7 @@ class Timer:
         b.record()
         torch.cuda.synchronize()
         one_ms = max(a.elapsed_time(b), 1e-3)
-        settle = int(min(2000, max(0, SETTLE_MS / one_ms - warmup)))
+        settle = int(min(20000, max(0, SETTLE_MS / one_ms - warmup)))
         for i in range(settle):
             fn(warmup + 1 + i)
         base = warmup + 1 + settle
@@ -381,13 +381,19 @@ def probe(torch, synth, args):
     """For rocprofv3 counter runs: 20 launches of one workload, then two kernels of known size (1 GiB):
     the library's streaming read, which issues the same 16-byte-per-lane loads as the MGLU kernels
     (read counters), and a plain device copy (write counters)."""
+    routed = args.probe.startswith("routed")
     if args.probe == "headline":
         name, cfg = HEADLINE, synth.config("large", n_masks=8, tokens=1)
+    elif routed:   # "routed decode_8b" / "routed large": top-2 of 8 on the planar mask format
+        name, cfg = args.probe, synth.config("large" if "large" in args.probe else "decode_8b", n_masks=8, tokens=1)
     else:
         name, cfg = next((n, c) for n, c, _, _, _ in extra_cases(synth) if args.probe in n)
-    w = Workload(name, cfg, swiglu=False)
+    w = Workload(name, cfg, swiglu=False, keep_inputs=routed)
+    if routed:
+        w.enable_routing(2)
+        w.enable_planar_routing(2, w.inputs[2])
     for i in range(20):
-        w.step(i)
+        (w.planar_routed_step if routed else w.step)(i)
     from paper_2506_23225_amd import api
     src = torch.empty(2 ** 30, dtype=torch.uint8, device="cuda:0")
     dst = torch.empty_like(src)
