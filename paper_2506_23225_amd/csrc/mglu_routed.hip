@@ -75,15 +75,68 @@ void stream_routed_kernel(RoutedParams p, int nw_shift)
     const int x_frags = (p.NC * Tr::TILES * 4) << tsh;
     f32x4 *lds_red = lds + resident_x_frags_padded(x_frags, nw_shift);
 
-    // ---- which masks did any token of this block select?  Lane (r, q) holds token tok0 + r. ----
-    const float *my_route = p.route + (long)(tok0 + min(r, tc - 1)) * p.n_masks;
+    // ---- Start-up, ordered so that nothing waits for more than it needs (loads complete in issue order): the
+    //      route weights first (a few words from L2), then the first R chunks of W (they do not depend on the
+    //      routing), then -- once the weights are there, W still in flight -- the selection and the selected
+    //      masks' words of those chunks, and last the copy of x into LDS. ----
+    const int n_my = (p.NC - wave + nw - 1) >> nw_shift;   // chunks this wavefront owns (NC >= nw)
+    auto kc_of = [&](int i) __attribute__((always_inline)) { return wave + i * nw; };
+    const float *my_route = p.route + (long)(tok0 + min(r, tc - 1)) * p.n_masks;   // lane (r, q) holds token tok0 + r
+    float w_all[kMaxMasks];
+#pragma unroll
+    for (int i = 0; i < kMaxMasks; ++i) w_all[i] = my_route[min(i, p.n_masks - 1)];
+    auto load_w = [&](chunk_t &c, int kc) __attribute__((always_inline)) {
+#pragma unroll
+        for (int t = 0; t < Tr::TILES; ++t)
+            c.w[t] = stream_load(reinterpret_cast<const frag *>(wbase + (long)kc * CHUNK_BYTES + t * 1024));
+    };
+    chunk_t buf[R];
+#pragma unroll
+    for (int s = 0; s < R; ++s) load_w(buf[s], kc_of(min(s, n_my - 1)));
+
+    // which masks did any token of this block select?
     uint32_t active = 0u;
-    for (int i = 0; i < p.n_masks; ++i)
-        if (__builtin_amdgcn_ballot_w64(r < tc && my_route[i] != 0.0f) != 0) active |= 1u << i;
+#pragma unroll
+    for (int i = 0; i < kMaxMasks; ++i)
+        if (__builtin_amdgcn_ballot_w64(i < p.n_masks && r < tc && w_all[i] != 0.0f) != 0) active |= 1u << i;
     active = __builtin_amdgcn_readfirstlane(active);   // the same in every wavefront: all read the same weights
     const int total = __builtin_popcount(active);
 
-    // ---- x of this token block into LDS, fragment order: f = (g << tsh) + row holds x[tok0 + row][g LANE_K ..) ----
+    // the first NACT selected masks in compact order; slots past the last selected mask repeat it (their loads
+    // stay in bounds, their sums are never formed); with nothing selected everything points at mask 0
+    const EpilogueParams ep = {p.n_masks, p.gate_fn, 0, p.route};
+    const uint32_t plane_bytes = (uint32_t)p.NC * (kWave * 4);
+    const int n_act = min(NACT, total);
+    uint32_t poff[NACT];   // byte offset of each selected mask's plane inside the column block (uniform)
+    float rw[NACT];        // this lane's token's weight for it
+    {
+        uint32_t rest = active;
+        int last = 0;
+#pragma unroll
+        for (int a = 0; a < NACT; ++a) {
+            const int i = rest ? __builtin_ctz(rest) : last;
+            last = i;
+            rest &= rest - 1;
+            poff[a] = (uint32_t)i * plane_bytes;
+            rw[a] = w_all[0];
+#pragma unroll
+            for (int m = 1; m < kMaxMasks; ++m) rw[a] = i == m ? w_all[m] : rw[a];
+            if (a >= n_act) rw[a] = 0.0f;
+        }
+    }
+    auto load_m = [&](chunk_t &c, int kc) __attribute__((always_inline)) {
+#pragma unroll
+        for (int a = 0; a < NACT; ++a)
+            c.m[a] = stream_load(reinterpret_cast<const uint32_t *>(mblock + (poff[a] + (uint32_t)kc * (kWave * 4)) + lane4));
+    };
+    auto load_chunk = [&](chunk_t &c, int kc) __attribute__((always_inline)) {
+        load_w(c, kc);
+        load_m(c, kc);
+    };
+#pragma unroll
+    for (int s = 0; s < R; ++s) load_m(buf[s], kc_of(min(s, n_my - 1)));
+
+    // x of this token block into LDS, fragment order: f = (g << tsh) + row holds x[tok0 + row][g LANE_K ..)
     for (int f = threadIdx.x; f < x_frags; f += nw * kWave) {
         const int row = min(f & ((1 << tsh) - 1), tc - 1), g = f >> tsh;
         const long k0 = min((long)g * Tr::LANE_K, (long)p.h - Tr::LANE_K);
@@ -93,42 +146,15 @@ void stream_routed_kernel(RoutedParams p, int nw_shift)
     }
     __syncthreads();
 
-    const int n_my = (p.NC - wave + nw - 1) >> nw_shift;   // chunks this wavefront owns (NC >= nw)
-    auto kc_of = [&](int i) __attribute__((always_inline)) { return wave + i * nw; };
-    const EpilogueParams ep = {p.n_masks, p.gate_fn, 0, p.route};
-    const uint32_t plane_bytes = (uint32_t)p.NC * (kWave * 4);
     f32x4 y = {0.f, 0.f, 0.f, 0.f};   // wavefront 0: the output
     f32x4 t_sum = {0.f, 0.f, 0.f, 0.f};   // wavefront 0: the reduced unmasked sum, kept for the masks beyond NACT
 
     if (total > 0) {
-        // ---- main pass: the first NACT selected masks in compact order; slots past the last selected
-        //      mask repeat it (their loads stay in bounds, their sums are never formed) ----
-        const int n_act = min(NACT, total);
-        uint32_t rest = active;
-        uint32_t poff[NACT];   // byte offset of each selected mask's plane inside the column block (uniform)
-        float rw[NACT];        // this lane's token's weight for it
-        int last = 0;
-#pragma unroll
-        for (int a = 0; a < NACT; ++a) {
-            const int i = rest ? __builtin_ctz(rest) : last;
-            last = i;
-            rest &= rest - 1;
-            poff[a] = (uint32_t)i * plane_bytes;
-            rw[a] = a < n_act ? my_route[i] : 0.0f;
-        }
-
+        // ---- main pass: W and the first NACT selected masks ----
         f32x4 acc[SETS];
 #pragma unroll
         for (int s = 0; s < SETS; ++s) acc[s] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-        auto load_chunk = [&](chunk_t &c, int kc) __attribute__((always_inline)) {
-#pragma unroll
-            for (int t = 0; t < Tr::TILES; ++t)
-                c.w[t] = stream_load(reinterpret_cast<const frag *>(wbase + (long)kc * CHUNK_BYTES + t * 1024));
-#pragma unroll
-            for (int a = 0; a < NACT; ++a)
-                c.m[a] = stream_load(reinterpret_cast<const uint32_t *>(mblock + (poff[a] + (uint32_t)kc * (kWave * 4)) + lane4));
-        };
         auto compute = [&](const chunk_t &c, int kc) __attribute__((always_inline)) {
 #pragma unroll
             for (int t = 0; t < Tr::TILES; ++t) {
@@ -139,10 +165,7 @@ void stream_routed_kernel(RoutedParams p, int nw_shift)
             }
         };
 
-        // ring of R register buffers, as in the resident kernel: every load is unconditional
-        chunk_t buf[R];
-#pragma unroll
-        for (int s = 0; s < R; ++s) load_chunk(buf[s], kc_of(min(s, n_my - 1)));
+        // ring of R register buffers, as in the resident kernel (filled above): every load is unconditional
         int i0 = 0;
         for (; i0 + 2 * R <= n_my; i0 += R) {
 #pragma unroll
