@@ -54,6 +54,9 @@
 #ifndef MGLU_RESIDENT_FLOOR
 #define MGLU_RESIDENT_FLOOR 1     // resident kernel: tell the register allocator how many wavefronts per SIMD to keep
 #endif
+#ifndef MGLU_RESIDENT_XPREFETCH
+#define MGLU_RESIDENT_XPREFETCH 1   // resident kernel: read x fragments from LDS one tile ahead, into registers zeroed once
+#endif
 #ifndef MGLU_STREAM_NONTEMPORAL
 #define MGLU_STREAM_NONTEMPORAL 1 // W and the masks are read once per call: mark the loads streaming
 #endif
@@ -332,7 +335,15 @@ __attribute__((amdgpu_waves_per_eu(resident_min_waves(Tr::ELEM_BYTES, MODE, NMP)
     // B-operand lanes past the last token: zero (predicated read), or in the RX flavour the last
     // token's row again; either way their accumulator columns are never stored
     const int rx = RX ? min(r, tc - 1) : r;
-    auto compute = [&](const chunk_t &c, int kc) __attribute__((always_inline)) {
+    const int n_my = (p.NC - wave + nw - 1) >> a_nw_shift;  // chunks this wavefront owns (NC >= nw, so >= 1)
+    auto kc_of = [&](int i) __attribute__((always_inline)) { return wave + i * nw; };
+    frag xq[2] = {frag{0, 0, 0, 0}, frag{0, 0, 0, 0}};
+    auto x_read = [&](frag &dst, int kc, int t) __attribute__((always_inline)) {
+        if (RX || r < tc) dst = lds_x[((((kc * Tr::TILES + t) * 4 + q)) << tsh) + rx];
+    };
+    // multiply this wavefront's i-th chunk (held in c)
+    auto compute = [&](const chunk_t &c, int i) __attribute__((always_inline)) {
+        const int kc = kc_of(i);
         if constexpr (MODE == kModeMgluVariant) {
 #pragma unroll
             for (int t = 0; t < Tr::TILES; ++t) {
@@ -344,6 +355,18 @@ __attribute__((amdgpu_waves_per_eu(resident_min_waves(Tr::ELEM_BYTES, MODE, NMP)
                     if (a >= n_act) break;  // uniform
                     acc[1 + a][0] = Tr::mma(Tr::template flip_at<NMP>(c.w[t], c.m, t, idx[a]), xf, acc[1 + a][0]);
                 }
+            }
+        } else if constexpr (MGLU_RESIDENT_XPREFETCH) {
+            // x fragments are read from LDS one tile ahead of their use, in turn into two registers sets that were
+            // zeroed once: the lanes past the last token are never written (predicated read), so they stay zero
+            // without being cleared for every tile, and the LDS latency hides behind the tile before.
+            const int kc_next = kc_of(min(i + 1, n_my - 1));
+#pragma unroll
+            for (int t = 0; t < Tr::TILES; ++t) {
+                if (t + 1 < Tr::TILES) x_read(xq[(t + 1) & 1], kc, t + 1);
+                else x_read(xq[0], kc_next, 0);
+                const frag xf[1] = {xq[t & 1]};
+                mma_tile<Tr, NMP, 1, MODE>(acc, c, t, xf);
             }
         } else {
 #pragma unroll
@@ -360,8 +383,6 @@ __attribute__((amdgpu_waves_per_eu(resident_min_waves(Tr::ELEM_BYTES, MODE, NMP)
     //      at once; otherwise a buffer is refilled right after it has been multiplied.  In the
     //      steady-state loop every load is unconditional, which lets the compiler wait for exactly
     //      the chunk it multiplies. ----
-    const int n_my = (p.NC - wave + nw - 1) >> a_nw_shift;  // chunks this wavefront owns (NC >= nw, so >= 1)
-    auto kc_of = [&](int i) __attribute__((always_inline)) { return wave + i * nw; };
     chunk_t buf[R];
     {
         // Copy this token block's x into LDS in fragment order: fragment f = (g << tsh) + row holds
@@ -397,12 +418,13 @@ __attribute__((amdgpu_waves_per_eu(resident_min_waves(Tr::ELEM_BYTES, MODE, NMP)
         }
         __syncthreads();
     }
+    if constexpr (MGLU_RESIDENT_XPREFETCH && MODE != kModeMgluVariant) x_read(xq[0], kc_of(0), 0);
 
     int i0 = 0;
     for (; i0 + 2 * R <= n_my; i0 += R) {  // every buffer of the ring has a chunk left to refill it
 #pragma unroll
         for (int s = 0; s < R; ++s) {
-            compute(buf[s], kc_of(i0 + s));
+            compute(buf[s], i0 + s);
             load_chunk(buf[s], kc_of(i0 + R + s));
         }
     }
@@ -410,13 +432,13 @@ __attribute__((amdgpu_waves_per_eu(resident_min_waves(Tr::ELEM_BYTES, MODE, NMP)
 #pragma unroll
     for (int s = 0; s < R; ++s) {
         if (i0 + s >= n_my) break;  // uniform over the wavefront
-        compute(buf[s], kc_of(i0 + s));
+        compute(buf[s], i0 + s);
         if (i0 + R + s < n_my) load_chunk(buf[s], kc_of(i0 + R + s));
     }
 #pragma unroll
     for (int s = 0; s < R; ++s) {
         if (i0 + R + s >= n_my) break;
-        compute(buf[s], kc_of(i0 + R + s));
+        compute(buf[s], i0 + R + s);
     }
 
     // ---- combine the K split and finish.  Sums are always added in wavefront order (fixed order =>

@@ -9,7 +9,7 @@ import itertools
 
 import torch
 
-from paper_2506_23225_amd import api
+from paper_2506_23225_amd import api, build
 
 DTYPES = {"bf16": torch.bfloat16, "f16": torch.float16, "f32": torch.float32}
 CALLS = ("forward", "forward_variant", "projections", "linear", "swiglu", "forward_routed")
@@ -26,6 +26,7 @@ SHAPES = ((264, 100), (1024, 25616), (136, 28672), (256, 14400), (8192, 64), (38
 
 def enumerate_plans():
     """{plan name: (cost, dtype name, call, n_masks, tokens, d_model, d_ff, route_k)} -- cheapest case per plan."""
+    build.build(force=False)   # host-only query, but the library has to exist (compiles only if it is absent or stale)
     best = {}
     for dname, call, n_m, T, (h, d) in itertools.product(DTYPES, CALLS, MASK_COUNTS, TOKENS, SHAPES):
         if call in ("linear", "swiglu") and n_m != 1:
