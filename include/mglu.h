@@ -102,9 +102,11 @@ mglu_status mglu_pack_masks(const mglu_desc *desc, const uint8_t *masks_dev, voi
 
 /* ---- the per-token path (Eq. 3; Alg. 1) -------------------------------------------------- */
 
-/* Bytes of scratch mglu_forward needs for this descriptor.  Every kernel of this version keeps its
- * partial sums in registers and LDS, so this is 0 for every descriptor; the argument pair stays in
- * the signatures so that a later version can ask for scratch without an interface change. */
+/* Bytes of scratch mglu_forward / mglu_forward_variant / mglu_ffn_forward need for this descriptor.
+ * 0 wherever one launch covers the layer (its partial sums stay in registers and LDS).  With 9 to 16
+ * masks and more tokens than the streaming kernels take (16-bit types, tokens > 16) the MFMA-tiled
+ * kernel runs twice, 8 masks per launch, and hands the fp32 sum of the first launch's terms to the
+ * second through the workspace: tokens * d_ff * 4 bytes.  0 also for an invalid descriptor. */
 size_t mglu_workspace_bytes(const mglu_desc *desc);
 
 /* out[tokens][d_ff] = MGLU_{n_masks}(x), Eq. 3 with g = Swish.

@@ -117,7 +117,7 @@ def mglu_pack_masks(desc, masks, packed=None):
 def _workspace(desc, device, workspace):
     need = mglu_workspace_bytes(desc)
     if workspace is None and need:
-        workspace = torch.zeros(need, dtype=torch.uint8, device=device)
+        workspace = torch.empty(need, dtype=torch.uint8, device=device)
     return workspace, (workspace.numel() if workspace is not None else 0)
 
 

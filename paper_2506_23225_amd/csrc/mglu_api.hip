@@ -145,7 +145,16 @@ struct Operands {
     float *proj_t, *proj_gate, *proj_value;
     int gate_fn, mask_use;
     const float *route;
+    void *workspace;
+    size_t workspace_bytes;
 };
+
+// fp32 [tokens][d_ff] for the MFMA-tiled kernel with more than 8 masks (two launches of 8 masks)
+size_t layer_workspace_bytes(const mglu_desc *d)
+{
+    if (d->n_masks <= 8 || !use_tiled_kernel(d, d->n_masks)) return 0;
+    return (size_t)d->tokens * d->d_ff * sizeof(float);
+}
 
 // The one place that picks the kernel family for a call: `mode` is a mglu::Mode.  With `describe` set
 // nothing is launched and the chosen kernel instantiation is written there instead.
@@ -158,6 +167,18 @@ mglu_status run_layer(const mglu_desc *d, int mode, const Operands &o, void *str
         pp.x = o.x; pp.w = o.w; pp.w2 = o.w2; pp.m = o.m; pp.out = o.out;
         pp.gate_fn = o.gate_fn; pp.mask_use = o.mask_use; pp.route = o.route;
         pp.describe = describe; pp.describe_len = describe_len;
+        if (mode == mglu::kModeMglu || mode == mglu::kModeMgluVariant) {
+            const size_t need = layer_workspace_bytes(d);
+            if (describe) {
+                pp.workspace = need ? reinterpret_cast<float *>(uintptr_t(256)) : nullptr;   // never dereferenced
+            } else if (need) {
+                if (!o.workspace || o.workspace_bytes < need)
+                    return fail(MGLU_ERR_WORKSPACE, "workspace has %zu bytes, this layer needs %zu (mglu_workspace_bytes)",
+                                o.workspace ? o.workspace_bytes : (size_t)0, need);
+                MGLU_TRY(check_ptr(o.workspace, "workspace_dev"));
+                pp.workspace = static_cast<float *>(o.workspace);
+            }
+        }
         return hip_result(mglu::launch_prefill(pp, elem_of(d), mode, static_cast<hipStream_t>(stream)), what);
     }
     mglu::StreamParams p = stream_params(d);
@@ -283,8 +304,8 @@ mglu_status mglu_pack_masks_planar(const mglu_desc *desc, const uint8_t *masks_d
 
 size_t mglu_workspace_bytes(const mglu_desc *desc)
 {
-    if (check_shape(desc, false) != MGLU_OK) return 0;
-    return 0;
+    if (check_shape(desc, true) != MGLU_OK) return 0;
+    return layer_workspace_bytes(desc);
 }
 
 mglu_status mglu_forward_variant(const mglu_desc *desc, const mglu_variant *variant, const void *x_dev,
@@ -296,8 +317,6 @@ mglu_status mglu_forward_variant(const mglu_desc *desc, const mglu_variant *vari
     MGLU_TRY(check_ptr(W_packed_dev, "W_packed_dev"));
     MGLU_TRY(check_ptr(masks_packed_dev, "masks_packed_dev"));
     MGLU_TRY(check_ptr(out_dev, "out_dev"));
-    (void)workspace_dev;
-    (void)workspace_bytes;
     int gate_fn = 0, mask_use = 0;
     const float *route = nullptr;
     if (variant) {
@@ -316,6 +335,7 @@ mglu_status mglu_forward_variant(const mglu_desc *desc, const mglu_variant *vari
     Operands o = {};
     o.x = x_dev; o.w = W_packed_dev; o.m = static_cast<const uint32_t *>(masks_packed_dev); o.out = out_dev;
     o.gate_fn = gate_fn; o.mask_use = mask_use; o.route = route;
+    o.workspace = workspace_dev; o.workspace_bytes = workspace_bytes;
     return run_layer(desc, mode, o, stream, "mglu_forward launch");
 }
 

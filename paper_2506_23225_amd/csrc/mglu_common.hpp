@@ -22,10 +22,13 @@
 // A lane's NMP words hold the NMP x 32 mask bits of the 32 weight elements that
 // lane holds in the chunk.  16-bit elements: they form 16 register pairs (tile t, pair p = e/2; low
 // half e even, high half e odd); the bit for (t, p, mask i, half hf) is in word
-// Half16Common::mask_word(t, p) at position mask_bit(t, p, i) + 16*hf, so one shift brings both
+// Half16Common::mask_word(t, p, i) at position mask_bit(t, p, i) + 16*hf, so one shift brings both
 // bits of a pair to the two sign positions 15 and 31.  For 2 to 16 masks the words are
-// assigned so that registers p and p + 2 (16 masks: p and p + 1) of a fragment find their bits in
-// two neighbouring words at the same position: one 64-bit shift then serves both.
+// assigned so that registers p and p + 2 of a fragment find their bits in two neighbouring words at
+// the same position: one 64-bit shift then serves both.  16 masks (16-bit elements) are two 8-mask
+// halves side by side: words 0-7 of a lane (pieces 0, 1) are masks 0-7 in the 8-mask order, words
+// 8-15 (pieces 2, 3) masks 8-15 -- a kernel built for 8 masks can read either half on its own
+// (chunk stride 4 KiB, half h at byte 2048 h), which is how the MFMA-tiled kernel runs 16 masks.
 // fp32: element E = 4t + e, linear = E*NMP + i -> word linear/32, bit linear%32.
 //
 //   planar masks  [jb][mask i < n_masks][kc][lane<64]  uint32
@@ -121,13 +124,14 @@ struct Half16Common {
             r[2] = w[2] ^ ((uint32_t)(a >> 32) & 0x80008000u);
             r[3] = w[3] ^ ((uint32_t)(b >> 32) & 0x80008000u);
         } else if constexpr (NMP == 16) {
-            // pair p: word 4t + p, bit i
-            const uint64_t m01 = shl64(((uint64_t)m[4 * t + 1] << 32) | m[4 * t], 15 - i);
-            const uint64_t m23 = shl64(((uint64_t)m[4 * t + 3] << 32) | m[4 * t + 2], 15 - i);
-            r[0] = w[0] ^ ((uint32_t)m01 & 0x80008000u);
-            r[1] = w[1] ^ ((uint32_t)(m01 >> 32) & 0x80008000u);
-            r[2] = w[2] ^ ((uint32_t)m23 & 0x80008000u);
-            r[3] = w[3] ^ ((uint32_t)(m23 >> 32) & 0x80008000u);
+            // two 8-mask halves side by side: mask i lives in words [8 (i/8), 8 (i/8) + 8) in the 8-mask order
+            const int o = 8 * (i >> 3) + 2 * t, s = i & 7;
+            const uint64_t mm = ((uint64_t)m[o + 1] << 32) | m[o];
+            const uint64_t a = shl64(mm, 15 - s), b = shl64(mm, 7 - s);
+            r[0] = w[0] ^ ((uint32_t)a & 0x80008000u);
+            r[1] = w[1] ^ ((uint32_t)b & 0x80008000u);
+            r[2] = w[2] ^ ((uint32_t)(a >> 32) & 0x80008000u);
+            r[3] = w[3] ^ ((uint32_t)(b >> 32) & 0x80008000u);
         } else if constexpr (NMP == 4) {
             // pair p: word 2(t/2) + p/2, bit ((t%2)*2 + p%2)*4 + i
             const uint64_t mm = ((uint64_t)m[2 * (t / 2) + 1] << 32) | m[2 * (t / 2)];
@@ -154,23 +158,37 @@ struct Half16Common {
     // Where the pack kernel puts the bit of (tile t, pair p, mask i) of a lane: word index and bit
     // position inside the low half of that word (the high half holds the pair's second element).
     template <int NMP>
-    __host__ __device__ static constexpr int mask_word(int t, int p)
+    __host__ __device__ static constexpr int mask_word(int t, int p, int i)
     {
-        return NMP == 16 ? 4 * t + p : NMP == 8 ? 2 * t + p / 2 : NMP == 4 ? 2 * (t / 2) + p / 2 : NMP == 2 ? p / 2 : 0;
+        return NMP == 16 ? 8 * (i / 8) + 2 * t + p / 2
+             : NMP == 8  ? 2 * t + p / 2
+             : NMP == 4  ? 2 * (t / 2) + p / 2
+             : NMP == 2  ? p / 2
+                         : 0;
     }
     template <int NMP>
     __host__ __device__ static constexpr int mask_bit(int t, int p, int i)
     {
-        return NMP == 16 ? i
+        return NMP == 16 ? (p % 2) * 8 + i % 8
              : NMP == 8  ? (p % 2) * 8 + i
              : NMP == 4  ? ((t % 2) * 2 + p % 2) * 4 + i
              : NMP == 2  ? (t * 2 + p % 2) * 2 + i
                          : 4 * t + p;
     }
+    // The same with a mask index that is only known at run time (uniform over the wavefront).  Below 16
+    // masks the word that holds a bit does not depend on i, only the shift does; with 16 the half is
+    // selected first.
     template <int NMP>
     __device__ static __forceinline__ frag flip_at(frag w, const uint32_t (&m)[NMP], int t, int i)
     {
-        return flip<NMP>(w, m, t, i);
+        if constexpr (NMP == 16) {
+            const bool hi = i >= 8;
+            const uint32_t half[8] = {hi ? m[8] : m[0],  hi ? m[9] : m[1],  hi ? m[10] : m[2], hi ? m[11] : m[3],
+                                      hi ? m[12] : m[4], hi ? m[13] : m[5], hi ? m[14] : m[6], hi ? m[15] : m[7]};
+            return flip<8>(w, half, t, i & 7);
+        } else {
+            return flip<NMP>(w, m, t, i);
+        }
     }
 
     // Planar mask format: one word holds the 32 bits of ONE mask for the 32 elements a lane holds in a
@@ -313,12 +331,15 @@ __host__ __device__ constexpr int sets_of(int mode, int nmp)
 //   gate_fn   0 Swish, 1 GELU (exact Gaussian CDF), 2 ReLU          ("Other Activation Functions")
 //   mask_use  bit 0: the gate branch is dense (x W), bit 1: the value branch is dense
 //             ("Partial Mask Ablation": 1 no gate mask, 2 no value mask, 3 no masks)
-//   route     null, or fp32 [tokens][n_masks] weights G(x)_i of the Top-K routed form
+//   route     null, or fp32 weights G(x)_i of the Top-K routed form: mask i of token tok at
+//             route[tok * route_stride + i] (the stride is the layer's mask count; n_masks here may be
+//             the count of a sub-range of masks that one launch covers)
 struct EpilogueParams {
     int n_masks;
     int gate_fn;
     int mask_use;
     const float *route;
+    int route_stride;
 };
 
 // Sign-flip form of the complement trick (Alg. 1 writes s_i and t - s_i): with
@@ -347,7 +368,7 @@ __device__ __forceinline__ void route_weights(const EpilogueParams &e, long tok,
     if (e.route && valid) {
 #pragma unroll
         for (int i = 0; i < NMP; ++i)
-            if (i < e.n_masks) rw[i] = e.route[tok * e.n_masks + i];
+            if (i < e.n_masks) rw[i] = e.route[tok * e.route_stride + i];
     }
 }
 

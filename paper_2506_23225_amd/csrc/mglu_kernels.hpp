@@ -39,6 +39,13 @@ struct PrefillParams {
     int gate_fn;          // epilogue variant: see EpilogueParams
     int mask_use;
     const float *route;   // [T][n_masks] route weights, may be null
+    float *workspace;     // fp32 [T][d], needed with more than 8 masks (two launches of 8 masks each)
+    // filled in by the launcher: which part of the layer's masks this launch covers
+    int mask_chunk_bytes; // bytes from one chunk's mask words to the next chunk's
+    int mask_offset;      // byte offset of this launch's masks inside a chunk's words
+    int route_stride;     // mask count of the layer (row stride of `route`)
+    const float *partial_in;   // fp32 [T][d] sum of the masks an earlier launch covered, added before rounding
+    float *partial_out;        // if set, the fp32 sum goes here instead of `out`
     char *describe;       // host only: see StreamParams
     size_t describe_len;
 };

@@ -73,7 +73,7 @@ __global__ __launch_bounds__(256) void pack_masks_kernel(PackParams p)
                 if (i >= p.n_masks) break;
                 const uint32_t bit = src[i * plane + off] != 0 ? 1u : 0u;
                 if constexpr (Tr::ELEM_BYTES == 2) {
-                    words[Tr::template mask_word<NMP>(t, e >> 1)] |=
+                    words[Tr::template mask_word<NMP>(t, e >> 1, i)] |=
                         bit << (Tr::template mask_bit<NMP>(t, e >> 1, i) + 16 * (e & 1));
                 } else {
                     const int lin = (4 * t + e) * NMP + i;         // element E = 4t + e

@@ -114,7 +114,7 @@ void prefill_kernel(PrefillParams p)
         const long jb = min(jb0 + cb, p.NB - 1);
         wbase[cb] = static_cast<const char *>(p.w) + jb * p.NC * CHUNK_BYTES;
         w2base[cb] = static_cast<const char *>(p.w2) + jb * p.NC * CHUNK_BYTES;
-        mbase[cb] = reinterpret_cast<const char *>(p.m) + jb * p.NC * (kWave * NMP * 4);
+        mbase[cb] = reinterpret_cast<const char *>(p.m) + jb * p.NC * p.mask_chunk_bytes + p.mask_offset;
     }
     const uint32_t lane_m = mask_lane_bytes<NMP>(lane);
 
@@ -174,7 +174,7 @@ void prefill_kernel(PrefillParams p)
 #pragma unroll
             for (int cb = 0; cb < CB; ++cb) {
                 const uint32_t *mp =
-                    reinterpret_cast<const uint32_t *>(mbase[cb] + (long)kc * (kWave * NMP * 4) + lane_m);
+                    reinterpret_cast<const uint32_t *>(mbase[cb] + (long)kc * p.mask_chunk_bytes + lane_m);
                 if constexpr (NMP >= 8) {
 #pragma unroll
                     for (int piece = 0; piece < NMP / 4; ++piece) {
@@ -428,8 +428,8 @@ void prefill_kernel(PrefillParams p)
             // plain mode: all NMP masks, a compile-time bound (a padding mask is all-value: its sum
             // equals t bit for bit, its gate is 0 and its term exactly 0)
             const EpilogueParams ep = MODE == kModeMgluVariant
-                                          ? EpilogueParams{p.n_masks, p.gate_fn, p.mask_use, p.route}
-                                          : EpilogueParams{NMP, 0, 0, nullptr};
+                                          ? EpilogueParams{p.n_masks, p.gate_fn, p.mask_use, p.route, p.route_stride}
+                                          : EpilogueParams{NMP, 0, 0, nullptr, 0};
             float rw[NMP];
             route_weights<NMP>(ep, tok, true, rw);
             f32x4 y;
@@ -447,6 +447,29 @@ void prefill_kernel(PrefillParams p)
                 }
             }
             const long o = tok * p.d + j0;
+            // a layer of more than 8 masks runs as two launches: the first leaves its fp32 sum in the
+            // workspace, the second adds it before the one rounding to the output type
+            if constexpr (MODE == kModeMglu || MODE == kModeMgluVariant) {
+                if (p.partial_in) {   // uniform
+                    if (full) {
+                        y += *reinterpret_cast<const f32x4 *>(p.partial_in + o);
+                    } else {
+#pragma unroll
+                        for (int c = 0; c < 4; ++c)
+                            if (j0 + c < p.d) y[c] += p.partial_in[o + c];
+                    }
+                }
+                if (p.partial_out) {  // uniform
+                    if (full) {
+                        *reinterpret_cast<f32x4 *>(p.partial_out + o) = y;
+                    } else {
+#pragma unroll
+                        for (int c = 0; c < 4; ++c)
+                            if (j0 + c < p.d) p.partial_out[o + c] = y[c];
+                    }
+                    continue;
+                }
+            }
             if (full) {
                 Tr::store4(p.out, o, y);
             } else {
@@ -471,9 +494,13 @@ static hipError_t launch_prefill_one(PrefillParams p, hipStream_t stream)
     const int per_xcd = (p.tiles_n + 7) / 8;
     const long wgs = (long)8 * per_xcd * p.tiles_m;
     const size_t lds = (size_t)kPrefillXBuf * 4 * TB * kWave * sizeof(f32x4);
+    if (p.mask_chunk_bytes == 0) {   // the launch covers all the layer's masks
+        p.mask_chunk_bytes = kWave * NMP * 4;
+        p.route_stride = p.n_masks;
+    }
     if (p.describe) {   // name the instantiation instead of launching it
-        snprintf(p.describe, p.describe_len, "prefill_kernel<%s, %d, %d, %d, %d, %d, %d>",
-                 traits_name<Tr>(), NMP, CB, TB, MODE, AD, NW);
+        snprintf(p.describe, p.describe_len, "prefill_kernel<%s, %d, %d, %d, %d, %d, %d>%s",
+                 traits_name<Tr>(), NMP, CB, TB, MODE, AD, NW, p.partial_in ? " twice" : "");
         return hipSuccess;
     }
     auto kern = prefill_kernel<Tr, NMP, CB, TB, MODE, AD, NW>;
@@ -547,7 +574,29 @@ static hipError_t launch_prefill_masks(const PrefillParams &p, hipStream_t strea
     case 2: return launch_prefill_best<Tr, 2, MODE, Tile<1, 8, 8, 2>, Tile<1, 8, 4, MGLU_PREFILL_AD_SMALL>>(p, stream);
     case 4: return launch_prefill_best<Tr, 4, MODE, Tile<1, 8, 8, 2>, Tile<1, 6, 8, 2>, Tile<1, 8, 4, 3>, Tile<1, 4, 4, MGLU_PREFILL_AD_SMALL>>(p, stream);
     case 8: return launch_prefill_best<Tr, 8, MODE, Tile<1, 4, 8, 2>, Tile<1, 4, 4, 3>>(p, stream);
-    default: return launch_prefill_best<Tr, 16, MODE, Tile<1, 2, 8, 2>, Tile<1, 2, 4, 3>>(p, stream);
+    default: {
+        // 9 to 16 masks: two launches of the 8-mask kernels, one per half of the 16-mask format (two 8-mask
+        // blocks side by side in every chunk).  The first leaves the fp32 sum of its masks' terms in the
+        // workspace, the second adds its own and rounds once.  18 accumulator sets' worth of multiplies
+        // instead of 17, at 64-token wavefront tiles instead of the 32 tokens that 17 sets would leave
+        // registers for (measured: 44 % of the matrix peak in one launch, 61 % for an 8-mask launch).
+        if (!p.workspace) return hipErrorInvalidValue;
+        PrefillParams a = p, b = p;
+        a.mask_chunk_bytes = b.mask_chunk_bytes = kWave * 16 * 4;
+        a.route_stride = b.route_stride = p.n_masks;
+        a.n_masks = 8;
+        a.mask_offset = 0;
+        a.partial_out = p.workspace;
+        b.n_masks = p.n_masks - 8;
+        b.mask_offset = kWave * 8 * 4;
+        b.partial_in = p.workspace;
+        if (p.route) b.route = p.route + 8;
+        if (!p.describe) {
+            const hipError_t e = launch_prefill_best<Tr, 8, MODE, Tile<1, 4, 8, 2>, Tile<1, 4, 4, 3>>(a, stream);
+            if (e != hipSuccess) return e;
+        }
+        return launch_prefill_best<Tr, 8, MODE, Tile<1, 4, 8, 2>, Tile<1, 4, 4, 3>>(b, stream);
+    }
     }
 }
 

@@ -104,7 +104,7 @@ void stream_routed_kernel(RoutedParams p, int nw_shift)
 
     // the first NACT selected masks in compact order; slots past the last selected mask repeat it (their loads
     // stay in bounds, their sums are never formed); with nothing selected everything points at mask 0
-    const EpilogueParams ep = {p.n_masks, p.gate_fn, 0, p.route};
+    const EpilogueParams ep = {p.n_masks, p.gate_fn, 0, p.route, p.n_masks};
     const uint32_t plane_bytes = (uint32_t)p.NC * (kWave * 4);
     const int n_act = min(NACT, total);
     uint32_t poff[NACT];   // byte offset of each selected mask's plane inside the column block (uniform)

@@ -167,8 +167,8 @@ __device__ __forceinline__ void mma_tile(f32x4 (&acc)[sets_of(MODE, NMP)][TB], c
 template <int MODE, int NMP>
 __device__ __forceinline__ EpilogueParams epilogue_params(const StreamParams &p)
 {
-    return MODE == kModeMgluVariant ? EpilogueParams{p.n_masks, p.gate_fn, p.mask_use, p.route}
-                                    : EpilogueParams{NMP, 0, 0, nullptr};
+    return MODE == kModeMgluVariant ? EpilogueParams{p.n_masks, p.gate_fn, p.mask_use, p.route, p.n_masks}
+                                    : EpilogueParams{NMP, 0, 0, nullptr, 0};
 }
 
 // Four consecutive outputs of one token, rounded once to the output type; the last columns of a ragged d_ff one by one.

@@ -37,6 +37,10 @@ def test_sizes_follow_the_memory_model(lib):
     d = _lib.MgluDesc(1, 200, 50, 1, _lib.MGLU_F32, _lib.MGLU_W_KN)
     assert lib.mglu_packed_weight_bytes(d) == 256 * 64 * 4
     assert lib.mglu_packed_mask_bytes(d) == 256 * 64 // 8
+    # scratch: only where the MFMA-tiled kernel runs a layer of more than 8 masks in two launches
+    for dtype, n_m, T, want in ((_lib.MGLU_BF16, 16, 4096, 4096 * 14336 * 4), (_lib.MGLU_F16, 9, 17, 17 * 14336 * 4),
+                                (_lib.MGLU_BF16, 8, 4096, 0), (_lib.MGLU_BF16, 16, 16, 0), (_lib.MGLU_F32, 16, 4096, 0)):
+        assert lib.mglu_workspace_bytes(_lib.MgluDesc(T, 4096, 14336, n_m, dtype, _lib.MGLU_W_KN)) == want
 
 
 def test_bad_arguments_are_reported_not_launched(lib):
@@ -57,6 +61,9 @@ def test_bad_arguments_are_reported_not_launched(lib):
         setattr(bad, field, value)
         assert fwd(bad) == code, (field, value, lib.mglu_last_error())
     assert lib.mglu_forward_bool(ok, fake, fake, fake, fake, fake, 16, None) == WORKSPACE
+    two_launches = _lib.MgluDesc(64, 256, 64, 16, _lib.MGLU_BF16, _lib.MGLU_W_KN)
+    assert fwd(two_launches) == WORKSPACE and b"mglu_workspace_bytes" in lib.mglu_last_error()
+    assert lib.mglu_forward(two_launches, fake, fake, fake, fake, fake, 64 * 64 * 4 - 1, None) == WORKSPACE
     # the allocation-free variant refuses layers beyond its static staging array, and bad pointers, before any GPU call
     big = _lib.MgluDesc(1, 4096, 14336, 8, _lib.MGLU_BF16, _lib.MGLU_W_KN)
     assert lib.mglu_forward_bool_static(big, fake, fake, fake, fake, None) == WORKSPACE

@@ -145,10 +145,12 @@ def test_fp16_panel_and_tiled_kernels(T, h, d, n_m):
     ("bf16", 1, 2048, 176, 16), ("bf16", 3, 520, 100, 9), ("bf16", 16, 384, 64, 12), ("bf16", 40, 640, 272, 16),
     ("bf16", 64, 256, 25616, 16), ("bf16", 130, 520, 200, 13), ("bf16", 300, 1024, 144, 16), ("f16", 2, 1024, 80, 16),
     ("f16", 200, 384, 136, 16), ("f32", 5, 264, 40, 16), ("f32", 33, 200, 24, 11),
+    ("bf16", 70, 392, 101, 10), ("f16", 129, 264, 50, 9),
 ])
 def test_nine_to_sixteen_masks(dtype, T, h, d, n_m):
-    """More than 8 masks (the paper's largest ablation has 16): 17 accumulator sets, mask words in four
-    pieces per chunk; through the resident, panel and tiled kernels."""
+    """More than 8 masks (the paper's largest ablation has 16): 17 accumulator sets and mask words in four
+    pieces per chunk in the resident and panel kernels; above 16 tokens the tiled kernel runs once per
+    8-mask half of the format with an fp32 hand-over (also with d_ff not a multiple of 4)."""
     x, W, masks = synth.make_inputs(h, d, n_m, T, dtype=dtype, seed=T + h + n_m, device=DEV)
     out = _run(x, W, masks)
     if d > 4096:
