@@ -249,7 +249,7 @@ mglu_status static_scratch(char **out)
 
 extern "C" {
 
-int mglu_format_version(void) { return 4; }
+int mglu_format_version(void) { return 5; }
 
 size_t mglu_packed_weight_bytes(const mglu_desc *desc)
 {
