@@ -10,9 +10,11 @@ pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
 
 
-@pytest.mark.parametrize("T", [1, 40, 200])
-def test_graph_replay_matches_eager(T):
-    h, d, n_m, layers = 512, 528, 4, 3
+@pytest.mark.parametrize("T,n_m", [(1, 4), (40, 4), (200, 4), (40, 16)])
+def test_graph_replay_matches_eager(T, n_m):
+    """(40 tokens, 16 masks: each layer is two launches of the tiled kernel with a hand-over through the
+    workspace, which the caller allocates before the capture.)"""
+    h, d, layers = 512, 528, 3
     packs, outs_eager = [], []
     x, W0, M0 = synth.make_inputs(h, d, n_m, T, dtype="bf16", seed=900 + T, device=DEV)
     desc = api.make_desc(T, h, d, n_m, x.dtype)
@@ -24,10 +26,11 @@ def test_graph_replay_matches_eager(T):
         packs.append((api.mglu_pack_weights(desc, W), api.mglu_pack_masks(desc, M), api.mglu_pack_weights(down, Wo)))
     hidden = torch.empty(T, d, dtype=x.dtype, device=DEV)
     acts = [x.clone()] + [torch.empty(T, h, dtype=x.dtype, device=DEV) for _ in range(layers)]
+    ws = torch.empty(max(api.mglu_workspace_bytes(desc), 16), dtype=torch.uint8, device=DEV)
 
     def chain():
         for layer, (Wp, Mp, Wop) in enumerate(packs):
-            api.mglu_ffn_forward(desc, acts[layer], Wp, Mp, Wop, hidden=hidden, y=acts[layer + 1])
+            api.mglu_ffn_forward(desc, acts[layer], Wp, Mp, Wop, hidden=hidden, y=acts[layer + 1], workspace=ws)
 
     chain()                                   # eager: also the first call of every kernel involved
     torch.cuda.synchronize()
