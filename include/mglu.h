@@ -104,7 +104,7 @@ mglu_status mglu_pack_masks(const mglu_desc *desc, const uint8_t *masks_dev, voi
 
 /* Bytes of scratch mglu_forward / mglu_forward_variant / mglu_ffn_forward need for this descriptor.
  * 0 wherever one launch covers the layer (its partial sums stay in registers and LDS).  With 9 to 16
- * masks and more tokens than the streaming kernels take (16-bit types, tokens > 16) the MFMA-tiled
+ * masks and more than 32 tokens (16-bit types) the MFMA-tiled
  * kernel runs twice, 8 masks per launch, and hands the fp32 sum of the first launch's terms to the
  * second through the workspace: tokens * d_ff * 4 bytes.  0 also for an invalid descriptor. */
 size_t mglu_workspace_bytes(const mglu_desc *desc);

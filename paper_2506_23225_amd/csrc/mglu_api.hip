@@ -152,7 +152,7 @@ struct Operands {
 // fp32 [tokens][d_ff] for the MFMA-tiled kernel with more than 8 masks (two launches of 8 masks)
 size_t layer_workspace_bytes(const mglu_desc *d)
 {
-    if (d->n_masks <= 8 || !use_tiled_kernel(d, d->n_masks)) return 0;
+    if (!use_tiled_kernel(d, d->n_masks) || !mglu::prefill_two_launches(d->n_masks, d->tokens)) return 0;
     return (size_t)d->tokens * d->d_ff * sizeof(float);
 }
 

@@ -85,6 +85,11 @@ struct PackParams {
 // would read W once per group of token blocks, and the 16-bit types hand over to the MFMA-tiled kernel.
 inline int stream_max_token_blocks(int nmp, int elem) { return elem == kElemF32 || nmp > 8 ? 1 : nmp <= 2 ? 4 : 2; }
 
+// Whether the MFMA-tiled kernel runs a layer as two launches of 8 masks each (and needs the fp32 workspace):
+// more than 8 masks and more tokens than the one 32-token tile that 17 accumulator sets leave registers for.
+// (Up to 32 tokens one launch reads W once; two would read it twice for nothing.)
+inline bool prefill_two_launches(int n_masks, int tokens) { return n_masks > 8 && tokens > 32; }
+
 // `elem` is an Elem (mglu_common.hpp): the element type of x, W and out
 hipError_t launch_stream(const StreamParams &p, int elem, int mode, hipStream_t stream);
 hipError_t launch_stream_read(const void *buf, size_t bytes, uint32_t *sink, hipStream_t stream);

@@ -109,12 +109,17 @@ void prefill_kernel(PrefillParams p)
     const char *wbase[CB];       // scalar: start of the column block's weight stream
     const char *w2base[CB];
     const char *mbase[CB];       // scalar: start of its mask words
+    // Only the 8-mask kernels are ever pointed at one half of a 16-mask layer (chunk stride and offset
+    // from the launcher, fp32 hand-over in the epilogue); the others keep the constants.
+    constexpr bool HALVES = NMP == 8 && (MODE == kModeMglu || MODE == kModeMgluVariant);
+    const int mask_chunk_bytes = HALVES ? p.mask_chunk_bytes : kWave * NMP * 4;
+    const int mask_offset = HALVES ? p.mask_offset : 0;
 #pragma unroll
     for (int cb = 0; cb < CB; ++cb) {
         const long jb = min(jb0 + cb, p.NB - 1);
         wbase[cb] = static_cast<const char *>(p.w) + jb * p.NC * CHUNK_BYTES;
         w2base[cb] = static_cast<const char *>(p.w2) + jb * p.NC * CHUNK_BYTES;
-        mbase[cb] = reinterpret_cast<const char *>(p.m) + jb * p.NC * p.mask_chunk_bytes + p.mask_offset;
+        mbase[cb] = reinterpret_cast<const char *>(p.m) + jb * p.NC * mask_chunk_bytes + mask_offset;
     }
     const uint32_t lane_m = mask_lane_bytes<NMP>(lane);
 
@@ -169,15 +174,23 @@ void prefill_kernel(PrefillParams p)
                     *reinterpret_cast<const frag *>(w2base[cb] + (long)kc * CHUNK_BYTES + t * 1024 + lane16);
         }
     };
-    auto load_masks = [&](int kc, int slot) __attribute__((always_inline)) {
+    // 16 masks: the words of a chunk are fetched in two parts -- part 0 = pieces 0 and 2 (tiles 0, 1 of either
+    // 8-mask half), part 1 = pieces 1 and 3 (tiles 2, 3) -- so that fewer than 32 mask registers are live at a time
+    // (32 spilled more).  Where W is fetched 2 tiles ahead (workgroups share it through L2) so is each part: 16
+    // live.  The shapes that stream W from HBM with a deeper prefetch keep the masks a whole chunk ahead, part
+    // by part: 24 live.
+    constexpr bool SPLIT16 = NMP == 16 && MODE != kModeSwiglu && MODE != kModeLinear;
+    constexpr bool SPLIT16_NEAR = SPLIT16 && AD <= 2;
+    auto load_masks = [&](int kc, int slot, int part = -1) __attribute__((always_inline)) {
         if constexpr (MODE != kModeSwiglu && MODE != kModeLinear) {
 #pragma unroll
             for (int cb = 0; cb < CB; ++cb) {
                 const uint32_t *mp =
-                    reinterpret_cast<const uint32_t *>(mbase[cb] + (long)kc * p.mask_chunk_bytes + lane_m);
+                    reinterpret_cast<const uint32_t *>(mbase[cb] + (long)kc * mask_chunk_bytes + lane_m);
                 if constexpr (NMP >= 8) {
 #pragma unroll
                     for (int piece = 0; piece < NMP / 4; ++piece) {
+                        if (part >= 0 && (piece & 1) != part) continue;   // compile time after inlining
                         u32x4 a = *reinterpret_cast<const u32x4 *>(reinterpret_cast<const char *>(mp) + piece * kMaskPieceBytes);
 #pragma unroll
                         for (int i = 0; i < 4; ++i) mk[slot][cb][4 * piece + i] = a[i];
@@ -198,6 +211,7 @@ void prefill_kernel(PrefillParams p)
 
     constexpr int A_LOADS = CB * (MODE == kModeSwiglu ? 2 : 1);   // load instructions of one load_a / load_masks
     constexpr int M_LOADS = (MODE == kModeSwiglu || MODE == kModeLinear) ? 0 : CB * (NMP >= 8 ? NMP / 4 : 1);
+    constexpr int M_PROLOGUE = SPLIT16_NEAR ? M_LOADS / 2 : (MR - 1) * M_LOADS;   // mask loads issued before the loop
     auto wait_vm = [](auto n) __attribute__((always_inline)) {
         asm volatile("s_waitcnt vmcnt(%0)" ::"n"(decltype(n)::value) : "memory");
     };
@@ -211,13 +225,13 @@ void prefill_kernel(PrefillParams p)
             for (int s = 0; s < XPIECES; ++s) stage_x(min(c, last), c, s);
         __builtin_amdgcn_sched_barrier(0);   // the x loads stay the oldest ones in flight
 #pragma unroll
-        for (int c = 0; c < MR - 1; ++c) load_masks(min(c, last), c);
+        for (int c = 0; c < MR - 1; ++c) load_masks(min(c, last), c, SPLIT16_NEAR ? 0 : -1);
 #pragma unroll
         for (int t = 0; t < AD; ++t) load_a(min(t / 4, last), t % 4, t % AR);
     }
     // Loads complete in issue order, so "at most the loads issued after them outstanding" means the x
     // fragments are in LDS; the compiler does not know that the hand-placed LDS reads depend on them.
-    wait_vm(std::integral_constant<int, (MR - 1) * M_LOADS + AD * A_LOADS>{});
+    wait_vm(std::integral_constant<int, M_PROLOGUE + AD * A_LOADS>{});
     __builtin_amdgcn_s_barrier();
 
     // One chunk of the K loop; PHASE = kc modulo the unroll (compile time): it fixes which entry of mk[]
@@ -278,7 +292,15 @@ void prefill_kernel(PrefillParams p)
                     stage_x(kx, (kc + kPrefillXAhead) & (kPrefillXBuf - 1), s);
             __builtin_amdgcn_sched_barrier(0);   // x first: the wait at the end of the chunk counts on it
             load_a(min(kc + (t + AD) / 4, last), (t + AD) % 4, (RS + t + AD) % AR);
-            if (t == 0) load_masks(kn, (MS + MR - 1) % MR);
+            if constexpr (SPLIT16_NEAR) {
+                if (t == 0) load_masks(kc, MS, 1);
+                if (t == 2) load_masks(kn, (MS + MR - 1) % MR, 0);
+            } else if constexpr (SPLIT16) {
+                if (t == 0) load_masks(kn, (MS + MR - 1) % MR, 0);
+                if (t == 2) load_masks(kn, (MS + MR - 1) % MR, 1);
+            } else {
+                if (t == 0) load_masks(kn, (MS + MR - 1) % MR);
+            }
             __builtin_amdgcn_sched_barrier(0);
 
             if constexpr (MASK_MAJOR) {
@@ -398,7 +420,8 @@ void prefill_kernel(PrefillParams p)
         // may still be outstanding (the A fragments of the tiles from that one on, and the masks if
         // that was the chunk's first tile)
         constexpr int XL = MGLU_PREFILL_XLOAD_TILE(XPIECES - 1, XPIECES);
-        wait_vm(std::integral_constant<int, (4 - XL) * A_LOADS + (XL == 0 ? M_LOADS : 0)>{});
+        constexpr int M_AFTER_X = SPLIT16 ? ((XL == 0 ? 1 : 0) + (XL <= 2 ? 1 : 0)) * (M_LOADS / 2) : (XL == 0 ? M_LOADS : 0);
+        wait_vm(std::integral_constant<int, (4 - XL) * A_LOADS + M_AFTER_X>{});
         // with two buffers every chunk ends in a barrier; with four only every second one (a buffer
         // is written two chunks after its last read and read two chunks after it was written, and
         // one barrier lies in between either way)
@@ -449,7 +472,7 @@ void prefill_kernel(PrefillParams p)
             const long o = tok * p.d + j0;
             // a layer of more than 8 masks runs as two launches: the first leaves its fp32 sum in the
             // workspace, the second adds it before the one rounding to the output type
-            if constexpr (MODE == kModeMglu || MODE == kModeMgluVariant) {
+            if constexpr (HALVES) {
                 if (p.partial_in) {   // uniform
                     if (full) {
                         y += *reinterpret_cast<const f32x4 *>(p.partial_in + o);
@@ -575,11 +598,13 @@ static hipError_t launch_prefill_masks(const PrefillParams &p, hipStream_t strea
     case 4: return launch_prefill_best<Tr, 4, MODE, Tile<1, 8, 8, 2>, Tile<1, 6, 8, 2>, Tile<1, 8, 4, 3>, Tile<1, 4, 4, MGLU_PREFILL_AD_SMALL>>(p, stream);
     case 8: return launch_prefill_best<Tr, 8, MODE, Tile<1, 4, 8, 2>, Tile<1, 4, 4, 3>>(p, stream);
     default: {
-        // 9 to 16 masks: two launches of the 8-mask kernels, one per half of the 16-mask format (two 8-mask
+        // 9 to 16 masks, more than 32 tokens: two launches of the 8-mask kernels, one per half of the 16-mask format (two 8-mask
         // blocks side by side in every chunk).  The first leaves the fp32 sum of its masks' terms in the
         // workspace, the second adds its own and rounds once.  18 accumulator sets' worth of multiplies
         // instead of 17, at 64-token wavefront tiles instead of the 32 tokens that 17 sets would leave
         // registers for (measured: 44 % of the matrix peak in one launch, 61 % for an 8-mask launch).
+        if (!prefill_two_launches(p.n_masks, p.T))
+            return launch_prefill_best<Tr, 16, MODE, Tile<1, 2, 8, 2>, Tile<1, 2, 4, 3>>(p, stream);
         if (!p.workspace) return hipErrorInvalidValue;
         PrefillParams a = p, b = p;
         a.mask_chunk_bytes = b.mask_chunk_bytes = kWave * 16 * 4;

@@ -37,9 +37,10 @@ def test_sizes_follow_the_memory_model(lib):
     d = _lib.MgluDesc(1, 200, 50, 1, _lib.MGLU_F32, _lib.MGLU_W_KN)
     assert lib.mglu_packed_weight_bytes(d) == 256 * 64 * 4
     assert lib.mglu_packed_mask_bytes(d) == 256 * 64 // 8
-    # scratch: only where the MFMA-tiled kernel runs a layer of more than 8 masks in two launches
-    for dtype, n_m, T, want in ((_lib.MGLU_BF16, 16, 4096, 4096 * 14336 * 4), (_lib.MGLU_F16, 9, 17, 17 * 14336 * 4),
-                                (_lib.MGLU_BF16, 8, 4096, 0), (_lib.MGLU_BF16, 16, 16, 0), (_lib.MGLU_F32, 16, 4096, 0)):
+    # scratch: only where the MFMA-tiled kernel runs a layer of more than 8 masks in two launches (more than 32 tokens)
+    for dtype, n_m, T, want in ((_lib.MGLU_BF16, 16, 4096, 4096 * 14336 * 4), (_lib.MGLU_F16, 9, 33, 33 * 14336 * 4),
+                                (_lib.MGLU_BF16, 8, 4096, 0), (_lib.MGLU_BF16, 16, 16, 0), (_lib.MGLU_BF16, 16, 32, 0),
+                                (_lib.MGLU_F32, 16, 4096, 0)):
         assert lib.mglu_workspace_bytes(_lib.MgluDesc(T, 4096, 14336, n_m, dtype, _lib.MGLU_W_KN)) == want
 
 
