@@ -230,6 +230,17 @@ def test_decode_8b_sixteen_masks_sampled():
     print("decode_8b n_m=16 rel err", _check_columns(x, W, masks, out, edge_columns(cfg["d_ff"])))
 
 
+def test_prefill_8b_sixteen_masks_sampled():
+    """4096 x 14336 with 16 masks at 4096 tokens, the benchmark's 16-mask prefill row: two launches of the
+    8-mask tiled kernel with the fp32 hand-over, all tokens on sampled columns."""
+    cfg = synth.config("prefill_8b", n_masks=16)
+    x, W, masks = synth.make_inputs(**cfg, seed=0, device=DEV)
+    assert api.mglu_describe_plan(api.make_desc(cfg["tokens"], 4096, 14336, 16, x.dtype)) == \
+        "prefill_kernel<Bf16Traits, 8, 1, 4, 0, 2, 8> twice"
+    out = _run(x, W, masks)
+    print("prefill_8b n_m=16 rel err", _check_columns(x, W, masks, out, edge_columns(cfg["d_ff"], n_random=8)))
+
+
 def test_prefill_8b_config_sampled():
     """Full-size prefill configuration: all 4096 tokens on sampled columns (tile edges, tail, random)."""
     cfg = synth.config("prefill_8b")
