@@ -324,6 +324,10 @@ def main():
                                       "mglu_over_swiglu_time": ms / sw["ms"],
                                       "byte_model_ratio": (16 + head_cfg["n_masks"]) / 32.0}
         result["measured_read_ceiling_GBps"] = 2 ** 30 / rd["ms"] / 1e6
+        # what a step costs with (next to) no work in it under this timing method: a 4 KiB read by the same kernel.
+        # Every row's time includes this launch-to-launch floor; it is reported, never subtracted.
+        floor = timer.run(lambda i: api.mglu_stream_read(timer.block_buf[:4096], timer.sink), 200, 20)
+        result["timing"]["empty_launch_us"] = floor["ms"] * 1e3
     if not args.no_cpu:
         result["cpu_baseline"] = cpu_baseline(head)
         result["gpu_over_cpu"] = result["value"] / result["cpu_baseline"]["value"]
