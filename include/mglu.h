@@ -115,8 +115,9 @@ size_t mglu_workspace_bytes(const mglu_desc *desc);
  *   masks_packed_dev from mglu_pack_masks with the same d_model, d_ff, n_masks, dtype
  *   out_dev          [tokens][d_ff], desc->dtype, fully overwritten (rounded once, to
  *                    nearest-even, after the sum over masks)
- *   workspace_dev    at least mglu_workspace_bytes(desc) bytes, may be NULL if that is 0;
- *                    contents need not be initialised and are not preserved.
+ *   workspace_dev    at least mglu_workspace_bytes(desc) bytes, 16-byte aligned, may be NULL if that is 0;
+ *                    contents need not be initialised and are not preserved; calls that may overlap on
+ *                    the GPU (different streams) need a workspace each.
  * The result is deterministic: the same inputs give the same bits on every call. */
 mglu_status mglu_forward(const mglu_desc *desc, const void *x_dev, const void *W_packed_dev,
                          const void *masks_packed_dev, void *out_dev,
