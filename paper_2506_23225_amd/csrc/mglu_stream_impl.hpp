@@ -668,6 +668,24 @@ void stream_panel_kernel(StreamParams p)
 
 struct PanelWide  { static constexpr int NWC = 8, NWK = 1, CPW = 2; };
 struct PanelSplit { static constexpr int NWC = 4, NWK = 2, CPW = 1; };
+// Split shapes for one token block of 16-bit elements: with a single token block the registers leave room for
+// three or four wavefronts per SIMD, and a launch of few workgroups (one per CU at most) streams faster with 12 or
+// 16 wavefronts per workgroup than with 8 (4096 x 14336, 16 tokens: 1 / 2 / 4 / 8 masks 64.6 / 64.3 / 68.3 / 63.9 %
+// of the HBM peak with two K-split wavefronts per column block, 72.8 / 71.2 / 69.5-70.8 / 65.1 % with 4 / 4 / 3 / 3;
+// four with 4 masks measured 67.0 %).
+struct PanelSplit3 { static constexpr int NWC = 4, NWK = 3, CPW = 1; };
+struct PanelSplit4 { static constexpr int NWC = 4, NWK = 4, CPW = 1; };
+// K-split wavefronts per column block of the split shape a launch of `tb` token blocks uses
+__host__ __device__ constexpr int split_nwk(bool is_f32, int nmp, int tb)
+{
+    return (is_f32 || tb != 1 || nmp > 8) ? PanelSplit::NWK : nmp <= 2 ? PanelSplit4::NWK : PanelSplit3::NWK;
+}
+template <typename Tr, int NMP, int TB>
+struct SplitShape {
+    static constexpr int kNwk = split_nwk(Tr::ELEM_BYTES == 4, NMP, TB);
+    typedef typename std::conditional<kNwk == 4, PanelSplit4,
+                                      typename std::conditional<kNwk == 3, PanelSplit3, PanelSplit>::type>::type type;
+};
 
 struct StreamPlan {
     bool resident;
@@ -711,7 +729,7 @@ static StreamPlan plan_stream(const StreamParams &p, int elem_kind, int nmp, int
     pl.tb = (blocks >= 4 && max_tb >= 4) ? 4 : (blocks >= 2 && max_tb >= 2) ? 2 : 1;
     pl.wide = ceil_div(p.NB, PanelWide::NWC) >= MGLU_PANEL_WIDE_MIN_WGS;
     const int nwc = pl.wide ? PanelWide::NWC : PanelSplit::NWC;
-    const int nwk = pl.wide ? PanelWide::NWK : PanelSplit::NWK;
+    const int nwk = pl.wide ? PanelWide::NWK : split_nwk(is_f32, nmp, pl.tb);
     const int cpw = pl.wide ? PanelWide::CPW : PanelSplit::CPW;
     const size_t xpanel = (size_t)2 * nwk * cpw * tiles * pl.tb * 1024;
     const size_t redp = (size_t)nwc * (nwk - 1) * sets * pl.tb * 1024;
@@ -761,7 +779,9 @@ template <typename Tr, int NMP, int MODE, typename Shape>
 static hipError_t launch_panel(const StreamParams &p, const StreamPlan &pl, hipStream_t stream)
 {
     constexpr bool kIsBf16 = Tr::ELEM_BYTES == 2;
-    if (pl.tb == 1) return launch_panel_one<Tr, NMP, 1, MODE, Shape>(p, pl, stream);
+    constexpr bool kSplit = std::is_same<Shape, PanelSplit>::value;
+    typedef typename std::conditional<kSplit, typename SplitShape<Tr, NMP, 1>::type, Shape>::type ShapeOne;
+    if (pl.tb == 1) return launch_panel_one<Tr, NMP, 1, MODE, ShapeOne>(p, pl, stream);
     if constexpr (kIsBf16 && NMP <= 8) {
         if (pl.tb == 2) return launch_panel_one<Tr, NMP, 2, MODE, Shape>(p, pl, stream);
         if constexpr (NMP <= 2) {
